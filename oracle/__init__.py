@@ -1,0 +1,248 @@
+"""CPU oracle for the Col-Bandit scoring path (ctypes front of colbandit_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg.  The product package never imports this module
+and this module never imports the product package.
+
+All arithmetic lives in the C file; this module only marshals numpy arrays.
+Citations (paper): MaxSim cell / score Eq. (1)-(2), (4)-(5); top-K Eq. (3);
+bounds Eq. (7)-(8) and Appendix A; Algorithm 1 and its detailed listing.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass, field
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "colbandit_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP across queries, no intrinsics)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.oracle_cell.restype = ctypes.c_double
+        _lib.oracle_rho.restype = ctypes.c_double
+        _lib.oracle_rho.argtypes = [ctypes.c_int, ctypes.c_int]
+        _lib.oracle_radius.restype = ctypes.c_double
+        _lib.oracle_radius.argtypes = [ctypes.c_double, ctypes.c_int, ctypes.c_double,
+                                       ctypes.c_int64, ctypes.c_double, ctypes.c_int]
+        _lib.oracle_splitmix64_next.restype = ctypes.c_uint64
+    return _lib
+
+
+def _p(a, ct):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def _f32(x):
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float32))
+
+
+def _i64(x):
+    return np.ascontiguousarray(np.asarray(x, dtype=np.int64))
+
+
+def _check(rc, what):
+    if rc < 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+    return rc
+
+
+def maxsim_cells(Q, E, offsets):
+    """H[N,T] in float64: Eq. (4)."""
+    Q, E, offsets = _f32(Q), _f32(E), _i64(offsets)
+    T, d = Q.shape
+    N = offsets.shape[0] - 1
+    H = np.empty((N, T), dtype=np.float64)
+    _check(_L().oracle_maxsim_cells(_p(Q, ctypes.c_float), T, d, _p(E, ctypes.c_float),
+                                    _p(offsets, ctypes.c_int64), ctypes.c_int64(N),
+                                    _p(H, ctypes.c_double)), "maxsim_cells")
+    return H
+
+
+def row_sums(H):
+    """S[N]: Eq. (5)."""
+    H = np.ascontiguousarray(H, dtype=np.float64)
+    N, T = H.shape
+    S = np.empty(N, dtype=np.float64)
+    _check(_L().oracle_row_sums(_p(H, ctypes.c_double), ctypes.c_int64(N), T,
+                                _p(S, ctypes.c_double)), "row_sums")
+    return S
+
+
+def topk(S, K, ids=None):
+    """First K of the (score desc, id asc) order: Eq. (3)."""
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    n = S.shape[0]
+    ids_a = None if ids is None else _i64(ids)
+    m = min(K, n)
+    out_ids = np.empty(m, dtype=np.int64)
+    out_s = np.empty(m, dtype=np.float64)
+    _check(_L().oracle_topk(_p(S, ctypes.c_double), _p(ids_a, ctypes.c_int64),
+                            ctypes.c_int64(n), K, _p(out_ids, ctypes.c_int64),
+                            _p(out_s, ctypes.c_double)), "topk")
+    return out_ids, out_s
+
+
+def rho(n, T):
+    return _L().oracle_rho(int(n), int(T))
+
+
+def radius(alpha, T, sigma, N, delta, n):
+    return _L().oracle_radius(float(alpha), int(T), float(sigma), int(N), float(delta), int(n))
+
+
+def bounds(vals, T, a, b, alpha, delta, N):
+    """dict(lcb, ucb, mean, sigma, radius, lb_hard, ub_hard) from revealed values."""
+    vals = np.ascontiguousarray(vals, dtype=np.float64)
+    out = np.empty(7, dtype=np.float64)
+    _check(_L().oracle_bounds(_p(vals, ctypes.c_double), int(vals.shape[0]), int(T),
+                              ctypes.c_double(a), ctypes.c_double(b), ctypes.c_double(alpha),
+                              ctypes.c_double(delta), ctypes.c_int64(N),
+                              _p(out, ctypes.c_double)), "bounds")
+    keys = ("lcb", "ucb", "mean", "sigma", "radius", "lb_hard", "ub_hard")
+    return dict(zip(keys, out.tolist()))
+
+
+def splitmix64_stream(state, count):
+    st = ctypes.c_uint64(state)
+    return [int(_L().oracle_splitmix64_next(ctypes.byref(st))) for _ in range(count)]
+
+
+def permutation(seed, query_index, T):
+    pi = np.empty(T, dtype=np.int32)
+    _check(_L().oracle_permutation(ctypes.c_uint64(seed & (2**64 - 1)),
+                                   ctypes.c_int64(query_index), int(T),
+                                   _p(pi, ctypes.c_int32)), "permutation")
+    return pi
+
+
+@dataclass
+class ColBanditResult:
+    topk_ids: np.ndarray
+    topk_scores: np.ndarray
+    final_ids: np.ndarray
+    rounds: int
+    counts: np.ndarray            # |A_r| entering each round, then after the last one
+    tau: np.ndarray               # [rounds]
+    cells_elim: int
+    cells_rescore: int
+    cells_unique: int
+    lcb: np.ndarray | None = None     # [rounds, N], NaN where inactive
+    ucb: np.ndarray | None = None
+    alive: np.ndarray | None = None   # [rounds, N] membership of A_{r+1}
+    extra: dict = field(default_factory=dict)
+
+
+def colbandit_from_H(H, K, M, B, alpha, delta, pi, a=-1.0, b=1.0, trace=True):
+    """Algorithm 1 over a given MaxSim matrix."""
+    H = np.ascontiguousarray(H, dtype=np.float64)
+    N, T = H.shape
+    pi = np.ascontiguousarray(pi, dtype=np.int32)
+    Rmax = (T + B - 1) // B
+    out_ids = np.full(K, -1, dtype=np.int64)
+    out_s = np.full(K, np.nan, dtype=np.float64)
+    final_ids = np.empty(N, dtype=np.int64)
+    n_final = ctypes.c_int64(0)
+    counts = np.full(Rmax + 1, -1, dtype=np.int64)
+    tau = np.full(Rmax, np.nan, dtype=np.float64)
+    cells = np.zeros(3, dtype=np.int64)
+    lcb = np.empty((Rmax, N), dtype=np.float64) if trace else None
+    ucb = np.empty((Rmax, N), dtype=np.float64) if trace else None
+    alive = np.empty((Rmax, N), dtype=np.uint8) if trace else None
+    rc = _check(_L().oracle_colbandit_from_H(
+        _p(H, ctypes.c_double), ctypes.c_int64(N), T, K, M, B,
+        ctypes.c_double(alpha), ctypes.c_double(delta), ctypes.c_double(a), ctypes.c_double(b),
+        _p(pi, ctypes.c_int32), _p(out_ids, ctypes.c_int64), _p(out_s, ctypes.c_double),
+        _p(final_ids, ctypes.c_int64), ctypes.byref(n_final), _p(counts, ctypes.c_int64),
+        _p(tau, ctypes.c_double), _p(lcb, ctypes.c_double), _p(ucb, ctypes.c_double),
+        _p(alive, ctypes.c_uint8), _p(cells, ctypes.c_int64)), "colbandit_from_H")
+    return ColBanditResult(out_ids, out_s, final_ids[: n_final.value].copy(), rc,
+                           counts[: rc + 1].copy(), tau[:rc].copy(),
+                           int(cells[0]), int(cells[1]), int(cells[2]),
+                           None if lcb is None else lcb[:rc],
+                           None if ucb is None else ucb[:rc],
+                           None if alive is None else alive[:rc].astype(bool))
+
+
+def colbandit_lazy(Q, E, offsets, K, M, B, alpha, delta, pi, a=-1.0, b=1.0):
+    """Algorithm 1 computing each revealed cell from the embeddings."""
+    Q, E, offsets = _f32(Q), _f32(E), _i64(offsets)
+    T, d = Q.shape
+    N = offsets.shape[0] - 1
+    pi = np.ascontiguousarray(pi, dtype=np.int32)
+    Rmax = (T + B - 1) // B
+    out_ids = np.full(K, -1, dtype=np.int64)
+    out_s = np.full(K, np.nan, dtype=np.float64)
+    final_ids = np.empty(N, dtype=np.int64)
+    n_final = ctypes.c_int64(0)
+    counts = np.full(Rmax + 1, -1, dtype=np.int64)
+    tau = np.full(Rmax, np.nan, dtype=np.float64)
+    cells = np.zeros(3, dtype=np.int64)
+    rc = _check(_L().oracle_colbandit_lazy(
+        _p(Q, ctypes.c_float), T, d, _p(E, ctypes.c_float), _p(offsets, ctypes.c_int64),
+        ctypes.c_int64(N), K, M, B, ctypes.c_double(alpha), ctypes.c_double(delta),
+        ctypes.c_double(a), ctypes.c_double(b), _p(pi, ctypes.c_int32),
+        _p(out_ids, ctypes.c_int64), _p(out_s, ctypes.c_double),
+        _p(final_ids, ctypes.c_int64), ctypes.byref(n_final), _p(counts, ctypes.c_int64),
+        _p(tau, ctypes.c_double), _p(cells, ctypes.c_int64)), "colbandit_lazy")
+    return ColBanditResult(out_ids, out_s, final_ids[: n_final.value].copy(), rc,
+                           counts[: rc + 1].copy(), tau[:rc].copy(),
+                           int(cells[0]), int(cells[1]), int(cells[2]))
+
+
+def num_threads():
+    return int(_L().oracle_num_threads())
+
+
+def full_batch(Q, E, offsets, K, want_scores=False):
+    """Exhaustive scoring of a query batch Q[nq,T,d], one thread per query."""
+    Q, E, offsets = _f32(Q), _f32(E), _i64(offsets)
+    nq, T, d = Q.shape
+    N = offsets.shape[0] - 1
+    S = np.empty((nq, N), dtype=np.float64) if want_scores else None
+    out_ids = np.empty((nq, K), dtype=np.int64)
+    out_s = np.empty((nq, K), dtype=np.float64)
+    _check(_L().oracle_full_batch(_p(Q, ctypes.c_float), nq, T, d, _p(E, ctypes.c_float),
+                                  _p(offsets, ctypes.c_int64), ctypes.c_int64(N), K,
+                                  _p(S, ctypes.c_double), _p(out_ids, ctypes.c_int64),
+                                  _p(out_s, ctypes.c_double)), "full_batch")
+    return out_ids, out_s, S
+
+
+def colbandit_batch(Q, E, offsets, K, M, B, alpha, delta, pi, a=-1.0, b=1.0):
+    """Col-Bandit (lazy reveals) for a query batch, one thread per query."""
+    Q, E, offsets = _f32(Q), _f32(E), _i64(offsets)
+    nq, T, d = Q.shape
+    N = offsets.shape[0] - 1
+    pi = np.ascontiguousarray(pi, dtype=np.int32).reshape(nq, T)
+    out_ids = np.empty((nq, K), dtype=np.int64)
+    out_s = np.empty((nq, K), dtype=np.float64)
+    cells = np.zeros((nq, 3), dtype=np.int64)
+    rounds = np.zeros(nq, dtype=np.int32)
+    _check(_L().oracle_colbandit_batch(
+        _p(Q, ctypes.c_float), nq, T, d, _p(E, ctypes.c_float), _p(offsets, ctypes.c_int64),
+        ctypes.c_int64(N), K, M, B, ctypes.c_double(alpha), ctypes.c_double(delta),
+        ctypes.c_double(a), ctypes.c_double(b), _p(pi, ctypes.c_int32),
+        _p(out_ids, ctypes.c_int64), _p(out_s, ctypes.c_double), _p(cells, ctypes.c_int64),
+        _p(rounds, ctypes.c_int32)), "colbandit_batch")
+    return out_ids, out_s, cells, rounds

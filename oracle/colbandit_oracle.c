@@ -1,0 +1,489 @@
+/*
+ * Plain CPU oracle for the Col-Bandit query-time scoring path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing in the product path may call, link or
+ * import this file: it exists so that tests, the smoke check and the
+ * benchmark's CPU-baseline leg have a slow, obviously correct statement of
+ * what the method computes.  It shares no code with the HIP library.
+ *
+ * Everything is scalar C in double precision.  Inputs are float arrays that
+ * already hold the storage-precision values (fp32, or bf16 values widened to
+ * float), so the only rounding here is that of double arithmetic.
+ *
+ * What follows the paper:
+ *   - MaxSim cell h(d,t) and score S(d;Q): Sec. 2.1, Eq. (1)-(2); matrix form
+ *     H and row sum S_i: Sec. 3.1, Eq. (4)-(5).
+ *   - exhaustive top-K: Sec. 2.1, Eq. (3).
+ *   - hard bounds, Bernstein-Serfling radius, hybrid interval: Sec. 4.1,
+ *     Eq. (7)-(8); empirical standard deviation, the n<=1 case, the
+ *     finite-population correction rho_n and c=1: Appendix A.
+ *   - batched progressive elimination, exact rescore of the survivors and
+ *     final top-K: Sec. 4.2, Algorithm 1 and its detailed listing in
+ *     Appendix "Detailed Algorithm Listing" with the walkthrough and the
+ *     complexity paragraph (cells touched).
+ *
+ * Readings taken where the paper is silent (each is listed in the design
+ * notes of the repository):
+ *   - log is the natural logarithm, c = 1, no O(1/n) term (Appendix A);
+ *   - the N inside the logarithm is the size of the candidate set handed to
+ *     the call and stays fixed over rounds;
+ *   - a document survives a round iff UCB >= tau (non-strict);
+ *   - the last batch holds the T mod B leftover tokens when B does not
+ *     divide T;
+ *   - every member of the final active set is rescored, however many;
+ *   - final order is (score descending, document index ascending);
+ *   - the reveal permutation comes from a SplitMix64-driven Fisher-Yates
+ *     shuffle defined in oracle_permutation() below.  PARITY UNPINNED with
+ *     respect to the authors' own generator: the paper fixes only that pi is
+ *     a uniform permutation drawn with a fixed seed.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG (-1)
+#define ORACLE_ERR_EMPTY_DOC (-2)
+#define ORACLE_ERR_NOMEM (-3)
+
+/* ------------------------------------------------------------------ */
+/* MaxSim cells and scores (Eq. (1)-(2), (4)-(5))                      */
+/* ------------------------------------------------------------------ */
+
+/* One cell: max over the document's tokens of <q_t, e_j>. */
+double oracle_cell(const float *Q, int t, int d, const float *E,
+                   const int64_t *off, int64_t i)
+{
+    const float *q = Q + (size_t)t * (size_t)d;
+    double best = -INFINITY;
+    for (int64_t j = off[i]; j < off[i + 1]; ++j) {
+        const float *e = E + (size_t)j * (size_t)d;
+        double dot = 0.0;
+        for (int k = 0; k < d; ++k)
+            dot += (double)q[k] * (double)e[k];
+        if (dot > best)
+            best = dot;
+    }
+    return best;
+}
+
+/* H[i*T+t] for all documents and query tokens. */
+int oracle_maxsim_cells(const float *Q, int T, int d, const float *E,
+                        const int64_t *off, int64_t N, double *H)
+{
+    if (!Q || !E || !off || !H || T < 1 || d < 1 || N < 0)
+        return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < N; ++i) {
+        if (off[i + 1] <= off[i])
+            return ORACLE_ERR_EMPTY_DOC;
+        for (int t = 0; t < T; ++t)
+            H[(size_t)i * T + t] = oracle_cell(Q, t, d, E, off, i);
+    }
+    return ORACLE_OK;
+}
+
+/* S_i = sum_t H[i][t], t ascending. */
+int oracle_row_sums(const double *H, int64_t N, int T, double *S)
+{
+    if (!H || !S || N < 0 || T < 1)
+        return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < N; ++i) {
+        double s = 0.0;
+        for (int t = 0; t < T; ++t)
+            s += H[(size_t)i * T + t];
+        S[i] = s;
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* exhaustive top-K (Eq. (3)): full sort by (score desc, id asc)       */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    double s;
+    int64_t id;
+} scored_t;
+
+static int cmp_scored(const void *pa, const void *pb)
+{
+    const scored_t *a = (const scored_t *)pa, *b = (const scored_t *)pb;
+    if (a->s > b->s) return -1;
+    if (a->s < b->s) return 1;
+    if (a->id < b->id) return -1;
+    if (a->id > b->id) return 1;
+    return 0;
+}
+
+/* ids may be NULL (then candidate k has id k).  Writes min(K,n) entries. */
+int oracle_topk(const double *S, const int64_t *ids, int64_t n, int K,
+                int64_t *out_ids, double *out_scores)
+{
+    if (!S || !out_ids || n < 0 || K < 0)
+        return ORACLE_ERR_ARG;
+    scored_t *v = (scored_t *)malloc(sizeof(scored_t) * (size_t)(n > 0 ? n : 1));
+    if (!v)
+        return ORACLE_ERR_NOMEM;
+    for (int64_t k = 0; k < n; ++k) {
+        v[k].s = S[k];
+        v[k].id = ids ? ids[k] : k;
+    }
+    qsort(v, (size_t)n, sizeof(scored_t), cmp_scored);
+    int64_t m = K < n ? K : n;
+    for (int64_t k = 0; k < m; ++k) {
+        out_ids[k] = v[k].id;
+        if (out_scores)
+            out_scores[k] = v[k].s;
+    }
+    free(v);
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* decision bounds (Sec. 4.1, Eq. (7)-(8); Appendix A)                 */
+/* ------------------------------------------------------------------ */
+
+/* Finite-population correction rho_n, piecewise in n <= T/2 (Appendix A). */
+double oracle_rho(int n, int T)
+{
+    if (2 * n <= T)
+        return 1.0 - (double)(n - 1) / (double)T;
+    return (1.0 - (double)n / (double)T) * (1.0 + 1.0 / (double)n);
+}
+
+/* Effective radius, Eq. (7), with c = 1; +inf when n <= 1 (Appendix A). */
+double oracle_radius(double alpha, int T, double sigma, int64_t N, double delta, int n)
+{
+    if (n <= 1)
+        return INFINITY;
+    double lg = log((double)N * (double)T / delta);
+    return alpha * (double)T * sigma * sqrt(2.0 * lg / (double)n) * sqrt(oracle_rho(n, T));
+}
+
+/*
+ * Interval of one document from its n revealed cell values (any order).
+ * out[0]=LCB out[1]=UCB out[2]=mean out[3]=sigma_hat out[4]=radius
+ * out[5]=LB_hard out[6]=UB_hard.  n == 0 gives the trivial [aT, bT].
+ */
+int oracle_bounds(const double *vals, int n, int T, double a, double b,
+                  double alpha, double delta, int64_t N, double *out)
+{
+    if (!out || n < 0 || n > T || (n > 0 && !vals))
+        return ORACLE_ERR_ARG;
+    double sum = 0.0;
+    for (int k = 0; k < n; ++k)
+        sum += vals[k];
+    double lbh = sum + (double)(T - n) * a;
+    double ubh = sum + (double)(T - n) * b;
+    if (n == 0) {
+        out[0] = a * T; out[1] = b * T; out[2] = 0.0; out[3] = 0.0;
+        out[4] = INFINITY; out[5] = lbh; out[6] = ubh;
+        return ORACLE_OK;
+    }
+    double mu = sum / (double)n;
+    double sigma = 0.0;
+    if (n > 1) {
+        double ss = 0.0;
+        for (int k = 0; k < n; ++k) {
+            double dv = vals[k] - mu;
+            ss += dv * dv;
+        }
+        sigma = sqrt(ss / (double)(n - 1));
+    }
+    double r = oracle_radius(alpha, T, sigma, N, delta, n);
+    double shat = (double)T * mu;
+    double lcb = shat - r, ucb = shat + r;
+    if (lbh > lcb) lcb = lbh;      /* max(LB_hard, S_hat - r) */
+    if (ubh < ucb) ucb = ubh;      /* min(UB_hard, S_hat + r) */
+    out[0] = lcb; out[1] = ucb; out[2] = mu; out[3] = sigma;
+    out[4] = r; out[5] = lbh; out[6] = ubh;
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* reveal permutation                                                  */
+/* ------------------------------------------------------------------ */
+
+/* SplitMix64 step (Steele, Lea, Flood 2014; public-domain reference). */
+uint64_t oracle_splitmix64_next(uint64_t *state)
+{
+    *state += 0x9E3779B97F4A7C15ULL;
+    uint64_t z = *state;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+/*
+ * Per-query permutation of [0,T): the generator state starts at
+ * seed + (query_index + 1) * 0x9E3779B97F4A7C15 (mod 2^64); then a
+ * Fisher-Yates shuffle walks i = T-1 .. 1 with j = next() mod (i+1).
+ */
+int oracle_permutation(uint64_t seed, int64_t query_index, int T, int32_t *pi)
+{
+    if (!pi || T < 1)
+        return ORACLE_ERR_ARG;
+    uint64_t st = seed + ((uint64_t)query_index + 1ULL) * 0x9E3779B97F4A7C15ULL;
+    for (int t = 0; t < T; ++t)
+        pi[t] = t;
+    for (int i = T - 1; i >= 1; --i) {
+        uint64_t j = oracle_splitmix64_next(&st) % (uint64_t)(i + 1);
+        int32_t tmp = pi[i];
+        pi[i] = pi[j];
+        pi[j] = tmp;
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Algorithm 1 (detailed listing)                                      */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    /* cell source: either a dense H (N x T) or the embeddings themselves */
+    const double *H;
+    const float *Q;
+    const float *E;
+    const int64_t *off;
+    int T, d;
+} cell_source_t;
+
+static double reveal(const cell_source_t *src, int64_t i, int t)
+{
+    if (src->H)
+        return src->H[(size_t)i * src->T + t];
+    return oracle_cell(src->Q, t, src->d, src->E, src->off, i);
+}
+
+static int cmp_desc(const void *pa, const void *pb)
+{
+    double a = *(const double *)pa, b = *(const double *)pb;
+    return (a > b) ? -1 : (a < b) ? 1 : 0;
+}
+
+/*
+ * The elimination loop, the rescore and the final top-K for one query.
+ *
+ * Outputs (any trace pointer may be NULL):
+ *   out_ids/out_scores [K]        estimated top-K, exact scores
+ *   final_ids [N], *n_final       final active set, index ascending
+ *   counts [Rmax+1]               |A_r| entering round r (counts[0]=N), then
+ *                                 the size after the last executed round
+ *   tau [Rmax]                    threshold of each executed round
+ *   tr_lcb, tr_ucb [Rmax x N]     interval of every document that was active
+ *                                 in the round (NaN for the others)
+ *   tr_alive [Rmax x N]           1 if the document is in A_{r+1}
+ *   cells [3]                     cells_elim, cells_rescore, cells_unique
+ * Rmax = ceil(T/B).  Returns the number of executed rounds (>= 0) or a
+ * negative error.
+ */
+static int colbandit_core(const cell_source_t *src, int64_t N, int K, int M, int B,
+                          double alpha, double delta, double a, double b,
+                          const int32_t *pi,
+                          int64_t *out_ids, double *out_scores,
+                          int64_t *final_ids, int64_t *n_final,
+                          int64_t *counts, double *tau,
+                          double *tr_lcb, double *tr_ucb, uint8_t *tr_alive,
+                          int64_t *cells)
+{
+    const int T = src->T;
+    if (N < 1 || K < 1 || K > N || M < 0 || B < 1 || !pi || !(alpha > 0.0) ||
+        !(delta > 0.0) || !(delta < 1.0) || !(a < b))
+        return ORACLE_ERR_ARG;
+    const int Rmax = (T + B - 1) / B;
+
+    int64_t *A = (int64_t *)malloc(sizeof(int64_t) * (size_t)N);      /* active set   */
+    double *vals = (double *)malloc(sizeof(double) * (size_t)N * T);  /* revealed     */
+    double *lcb = (double *)malloc(sizeof(double) * (size_t)N);
+    double *ucb = (double *)malloc(sizeof(double) * (size_t)N);
+    double *srt = (double *)malloc(sizeof(double) * (size_t)N);
+    double *S = (double *)malloc(sizeof(double) * (size_t)N);
+    if (!A || !vals || !lcb || !ucb || !srt || !S) {
+        free(A); free(vals); free(lcb); free(ucb); free(srt); free(S);
+        return ORACLE_ERR_NOMEM;
+    }
+    int64_t nA = N;
+    for (int64_t i = 0; i < N; ++i) {
+        A[i] = i;
+        lcb[i] = a * T;     /* trivial initial interval */
+        ucb[i] = b * T;
+    }
+    if (tr_lcb)
+        for (size_t x = 0; x < (size_t)Rmax * N; ++x) tr_lcb[x] = NAN;
+    if (tr_ucb)
+        for (size_t x = 0; x < (size_t)Rmax * N; ++x) tr_ucb[x] = NAN;
+    if (tr_alive)
+        memset(tr_alive, 0, (size_t)Rmax * N);
+
+    int n = 0;              /* revealed cells per active document (same for all) */
+    int r = 1;
+    int64_t cells_elim = 0;
+    if (counts) counts[0] = N;
+
+    while (nA > (int64_t)K + M && (r - 1) * B < T) {
+        int lo = (r - 1) * B;
+        int hi = r * B < T ? r * B : T;            /* batch pi[lo..hi) */
+        for (int64_t x = 0; x < nA; ++x) {
+            int64_t i = A[x];
+            for (int p = lo; p < hi; ++p)
+                vals[(size_t)i * T + p] = reveal(src, i, pi[p]);
+        }
+        cells_elim += (int64_t)(hi - lo) * nA;
+        n = hi;
+        for (int64_t x = 0; x < nA; ++x) {
+            int64_t i = A[x];
+            double o[7];
+            oracle_bounds(vals + (size_t)i * T, n, T, a, b, alpha, delta, N, o);
+            lcb[i] = o[0];
+            ucb[i] = o[1];
+            srt[x] = o[0];
+            if (tr_lcb) tr_lcb[(size_t)(r - 1) * N + i] = o[0];
+            if (tr_ucb) tr_ucb[(size_t)(r - 1) * N + i] = o[1];
+        }
+        qsort(srt, (size_t)nA, sizeof(double), cmp_desc);
+        double th = srt[K - 1];                     /* K-th largest LCB */
+        if (tau) tau[r - 1] = th;
+        int64_t m = 0;
+        for (int64_t x = 0; x < nA; ++x) {
+            int64_t i = A[x];
+            if (ucb[i] >= th) {
+                A[m++] = i;
+                if (tr_alive) tr_alive[(size_t)(r - 1) * N + i] = 1;
+            }
+        }
+        nA = m;
+        if (counts) counts[r] = nA;
+        ++r;
+    }
+    const int rounds = r - 1;
+
+    /* exact rescore of every survivor on all T tokens */
+    for (int64_t x = 0; x < nA; ++x) {
+        int64_t i = A[x];
+        double s = 0.0;
+        for (int t = 0; t < T; ++t)
+            s += reveal(src, i, t);
+        S[x] = s;
+    }
+    int rc = oracle_topk(S, A, nA, K, out_ids, out_scores);
+
+    if (final_ids)
+        for (int64_t x = 0; x < nA; ++x) final_ids[x] = A[x];
+    if (n_final) *n_final = nA;
+    if (cells) {
+        cells[0] = cells_elim;
+        cells[1] = (int64_t)T * nA;
+        cells[2] = cells_elim + (int64_t)(T - n) * nA;
+    }
+    free(A); free(vals); free(lcb); free(ucb); free(srt); free(S);
+    return rc < 0 ? rc : rounds;
+}
+
+/* Col-Bandit over a given dense MaxSim matrix H (N x T). */
+int oracle_colbandit_from_H(const double *H, int64_t N, int T, int K, int M, int B,
+                            double alpha, double delta, double a, double b,
+                            const int32_t *pi,
+                            int64_t *out_ids, double *out_scores,
+                            int64_t *final_ids, int64_t *n_final,
+                            int64_t *counts, double *tau,
+                            double *tr_lcb, double *tr_ucb, uint8_t *tr_alive,
+                            int64_t *cells)
+{
+    if (!H || T < 1)
+        return ORACLE_ERR_ARG;
+    cell_source_t src = {H, NULL, NULL, NULL, T, 0};
+    return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, out_ids, out_scores,
+                          final_ids, n_final, counts, tau, tr_lcb, tr_ucb, tr_alive, cells);
+}
+
+/* Col-Bandit that computes each revealed cell from the embeddings. */
+int oracle_colbandit_lazy(const float *Q, int T, int d, const float *E,
+                          const int64_t *off, int64_t N, int K, int M, int B,
+                          double alpha, double delta, double a, double b,
+                          const int32_t *pi,
+                          int64_t *out_ids, double *out_scores,
+                          int64_t *final_ids, int64_t *n_final,
+                          int64_t *counts, double *tau, int64_t *cells)
+{
+    if (!Q || !E || !off || T < 1 || d < 1)
+        return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < N; ++i)
+        if (off[i + 1] <= off[i])
+            return ORACLE_ERR_EMPTY_DOC;
+    cell_source_t src = {NULL, Q, E, off, T, d};
+    return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, out_ids, out_scores,
+                          final_ids, n_final, counts, tau, NULL, NULL, NULL, cells);
+}
+
+/* ------------------------------------------------------------------ */
+/* query batches: one thread per query, as in the paper's threading    */
+/* model (Appendix "Multi-threading model")                            */
+/* ------------------------------------------------------------------ */
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Exhaustive scores + top-K for nq queries.  S [nq x N] may be NULL. */
+int oracle_full_batch(const float *Q, int nq, int T, int d, const float *E,
+                      const int64_t *off, int64_t N, int K,
+                      double *S, int64_t *out_ids, double *out_scores)
+{
+    if (!Q || !E || !off || nq < 1 || T < 1 || d < 1 || N < 1 || K < 0 || K > N)
+        return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < N; ++i)
+        if (off[i + 1] <= off[i])
+            return ORACLE_ERR_EMPTY_DOC;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int q = 0; q < nq; ++q) {
+        const float *Qq = Q + (size_t)q * T * d;
+        double *Sq = S ? S + (size_t)q * N : (double *)malloc(sizeof(double) * (size_t)N);
+        if (!Sq) { err = ORACLE_ERR_NOMEM; continue; }
+        for (int64_t i = 0; i < N; ++i) {
+            double s = 0.0;
+            for (int t = 0; t < T; ++t)
+                s += oracle_cell(Qq, t, d, E, off, i);
+            Sq[i] = s;
+        }
+        if (K > 0 && out_ids)
+            oracle_topk(Sq, NULL, N, K, out_ids + (size_t)q * K,
+                        out_scores ? out_scores + (size_t)q * K : NULL);
+        if (!S) free(Sq);
+    }
+    return err;
+}
+
+/* Col-Bandit (lazy reveals) for nq queries; pi is [nq x T].  cells [nq x 3],
+ * rounds [nq] may be NULL. */
+int oracle_colbandit_batch(const float *Q, int nq, int T, int d, const float *E,
+                           const int64_t *off, int64_t N, int K, int M, int B,
+                           double alpha, double delta, double a, double b,
+                           const int32_t *pi, int64_t *out_ids, double *out_scores,
+                           int64_t *cells, int32_t *rounds)
+{
+    if (!Q || !E || !off || !pi || !out_ids || nq < 1)
+        return ORACLE_ERR_ARG;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int q = 0; q < nq; ++q) {
+        int rc = oracle_colbandit_lazy(Q + (size_t)q * T * d, T, d, E, off, N, K, M, B,
+                                       alpha, delta, a, b, pi + (size_t)q * T,
+                                       out_ids + (size_t)q * K,
+                                       out_scores ? out_scores + (size_t)q * K : NULL,
+                                       NULL, NULL, NULL, NULL,
+                                       cells ? cells + (size_t)q * 3 : NULL);
+        if (rc < 0) err = rc;
+        else if (rounds) rounds[q] = rc;
+    }
+    return err;
+}
