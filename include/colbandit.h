@@ -1,0 +1,189 @@
+/*
+ * colbandit.h - C-ABI of the MI355X-native Col-Bandit scoring library.
+ *
+ * Two scoring paths over one packed, ragged corpus of token embeddings:
+ *
+ *   colbandit_full_maxsim  exhaustive late-interaction scoring.  Cell (i,t) of the
+ *                          MaxSim matrix is max_j <q_t, e_{i,j}> (paper Eq. (1)/(4)),
+ *                          a document's score is the row sum (Eq. (2)/(5)), and the
+ *                          result is the top-K of the scores (Eq. (3)).
+ *   colbandit_topk         the Col-Bandit estimator of that top-K (Sec. 4, Algorithm 1
+ *                          and its detailed listing in the implementation appendix):
+ *                          batched cell reveals in a seeded order shared by all
+ *                          documents of a query, per-document Bernstein-Serfling
+ *                          intervals (Eq. (7)-(8), Appendix A), elimination of every
+ *                          document whose UCB is below the K-th largest LCB, exact
+ *                          rescoring of the survivors and a final top-K.
+ *
+ * Conventions common to all entry points
+ *   - Pointers documented as DEVICE point to memory of the current HIP device, owned
+ *     by the caller; the library never frees or keeps them.  HOST pointers are plain
+ *     process memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     kernels are enqueued on it.  Unless stated otherwise a call returns after
+ *     enqueueing; outputs are valid once the caller has synchronised the stream.
+ *   - Return value: COLBANDIT_OK (0) or a negative COLBANDIT_ERR_* code.  On an
+ *     argument error nothing is enqueued and no output is written.
+ *   - Layout: Q is [n_queries][T][d] row-major; doc_tokens is [total_tokens][d]
+ *     row-major with document i owning rows doc_offsets[i] .. doc_offsets[i+1]-1;
+ *     both in the storage type `dt`.  Q and doc_tokens must be 16-byte aligned.
+ *   - Preconditions the host cannot check without a copy: doc_offsets is
+ *     non-decreasing, doc_offsets[0] >= 0, doc_offsets[N] <= total_tokens and every
+ *     document has at least one token.  Kernels clamp row indices into
+ *     [0,total_tokens), so a violation gives meaningless scores, never an
+ *     out-of-bounds access; colbandit_validate_offsets checks them on the device.
+ */
+#ifndef COLBANDIT_H
+#define COLBANDIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { COLBANDIT_F32 = 0, COLBANDIT_BF16 = 1 } colbandit_dtype;
+
+enum {
+    COLBANDIT_OK = 0,
+    COLBANDIT_ERR_NULL = -1,         /* a required pointer is NULL                    */
+    COLBANDIT_ERR_SHAPE = -2,        /* n_queries, T, d, N, total_tokens or K invalid */
+    COLBANDIT_ERR_KNOB = -3,         /* alpha_ef, delta, M, B or [a,b] out of range   */
+    COLBANDIT_ERR_UNSUPPORTED = -4,  /* valid request outside what the kernels cover  */
+    COLBANDIT_ERR_WORKSPACE = -5,    /* workspace or trace buffer too small           */
+    COLBANDIT_ERR_ALIGNMENT = -6,    /* Q / doc_tokens / workspace misaligned         */
+    COLBANDIT_ERR_HIP = -7,          /* a HIP runtime call failed                     */
+    COLBANDIT_ERR_BAD_OFFSETS = -8   /* colbandit_validate_offsets found a violation  */
+};
+
+/* Limits of this build (requests beyond them return COLBANDIT_ERR_UNSUPPORTED). */
+#define COLBANDIT_MAX_T 128          /* query tokens                                  */
+#define COLBANDIT_MAX_K 1024         /* size of the returned top-K                    */
+#define COLBANDIT_MAX_B 16           /* cells revealed per document per round         */
+#define COLBANDIT_MAX_ROUNDS 64      /* ceil(T/B)                                     */
+
+/*
+ * Optional knobs of colbandit_topk.  A zero-initialised struct selects the paper's
+ * deployed defaults (implementation appendix, "Default parameter setting").
+ */
+typedef struct {
+    int B;              /* round size; 0 -> 4 (Sec. 4.2)                               */
+    float a, b;         /* support [a,b] of a cell; a == b == 0 -> [-1,1] (Sec. 4.1)   */
+    const int32_t *pi;  /* DEVICE [n_queries][T] reveal orders, each a permutation of
+                           0..T-1; NULL -> drawn on the device from `seed`, see
+                           colbandit_permutation                                        */
+    void *trace;        /* DEVICE buffer of colbandit_trace_bytes() bytes or NULL;
+                           test aid, layout below                                       */
+    size_t trace_bytes;
+    int force_gather;   /* nonzero: reveal round 1 with the gather kernel as well
+                           (test aid; the default picks the dense kernel for bf16)      */
+} colbandit_opts;
+
+/*
+ * Per-query statistics, HOST memory (Sec. 3.1 coverage; implementation appendix,
+ * "Complexity": cells touched = sum_r |B_r||A_r| + T|A_final|).
+ */
+typedef struct {
+    int32_t rounds;                                   /* elimination rounds executed   */
+    int32_t survivors[COLBANDIT_MAX_ROUNDS + 2];      /* |A_1| = N, then |A_{r+1}|
+                                                         after each executed round     */
+    int64_t cells_elim;                               /* sum_r |B_r| |A_r|             */
+    int64_t cells_rescore;                            /* T |A_final|                   */
+    int64_t cells_unique;                             /* |Omega| with set semantics    */
+    float ms_total;                                   /* device time of the whole call
+                                                         (all queries of the batch)    */
+} colbandit_stats;
+
+/*
+ * Trace buffer layout (R = ceil(T/B) rounds, nq = n_queries), in this order:
+ *   int32   count[(R+1)][nq]     |A| entering round r+1 (count[0] = N)
+ *   float   tau[R][nq]           threshold of each executed round (NaN if not run)
+ *   float   lcb[R][nq][N]        interval of every document active in the round,
+ *   float   ucb[R][nq][N]        NaN elsewhere
+ *   uint8   alive[R][nq][N]      1 iff the document is in the next active set
+ */
+size_t colbandit_trace_bytes(int n_queries, int T, int B, int64_t N);
+
+/* Scratch the two scoring calls need for these sizes (bytes; 0 on invalid sizes). */
+size_t colbandit_workspace_bytes(int n_queries, int T, int d, int64_t N,
+                                 int64_t total_tokens, int K, int M);
+
+/*
+ * Exhaustive Full-MaxSim (Eq. (1)-(3)).
+ *   Q, doc_tokens, doc_offsets   DEVICE, see layout above; doc_offsets is int64 [N+1]
+ *   K                            0 -> scores only; else 1 <= K <= min(N, MAX_K)
+ *   scores                       DEVICE float [n_queries][N], fp32 row sums; may be
+ *                                NULL when K > 0 (then they live in the workspace)
+ *   topk_ids, topk_scores        DEVICE int64 / float [n_queries][K], ordered by
+ *                                (score descending, document index ascending);
+ *                                required when K > 0
+ *   cells                        DEVICE float [n_queries][N][T] or NULL: the MaxSim
+ *                                matrix itself (test aid)
+ *   workspace                    DEVICE, 256-byte aligned, >= colbandit_workspace_bytes
+ * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; fp32 inputs
+ * use fp32 matrix instructions.  Fully asynchronous.
+ */
+int colbandit_full_maxsim(const void *Q, int n_queries, int T, int d, colbandit_dtype dt,
+                          const void *doc_tokens, const int64_t *doc_offsets, int64_t N,
+                          int64_t total_tokens, int K, float *scores, int64_t *topk_ids,
+                          float *topk_scores, float *cells, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/*
+ * Col-Bandit top-K (Algorithm 1).
+ *   K              1 <= K <= min(N, MAX_K)
+ *   alpha_ef       relaxation of the radius, 0 < alpha_ef <= 1 (Eq. (7))
+ *   delta          0 < delta < 1
+ *   M              rescore margin, >= 0: the loop stops once |A| <= K + M
+ *   seed           seed of the per-query reveal permutations (ignored if opts->pi)
+ *   opts           HOST, may be NULL
+ *   topk_ids       DEVICE int64 [n_queries][K]; entries beyond the number of
+ *                  survivors (possible only if cells leave [a,b]) are -1
+ *   topk_scores    DEVICE float [n_queries][K]: exact scores of the survivors,
+ *                  computed by the same kernel arithmetic as colbandit_full_maxsim
+ *                  (same bits); -inf where the id is -1
+ *   stats          HOST [n_queries] or NULL.  When non-NULL the call synchronises
+ *                  the stream before returning; otherwise it is fully asynchronous
+ *                  (all round control stays on the device).
+ * Queries are independent: each has its own permutation, active set and stopping
+ * round; the batch only shares kernel launches.
+ */
+int colbandit_topk(const void *Q, int n_queries, int T, int d, colbandit_dtype dt,
+                   const void *doc_tokens, const int64_t *doc_offsets, int64_t N,
+                   int64_t total_tokens, int K, float alpha_ef, float delta, int M,
+                   uint64_t seed, const colbandit_opts *opts, int64_t *topk_ids,
+                   float *topk_scores, colbandit_stats *stats, void *workspace,
+                   size_t workspace_bytes, void *stream);
+
+/*
+ * The reveal order used for query `query_index` under `seed` (Sec. 4.2: one uniform
+ * permutation of [T] per query, fixed seed; the generator itself is this library's
+ * choice): SplitMix64 started at seed + (query_index+1)*0x9E3779B97F4A7C15, then a
+ * Fisher-Yates shuffle for i = T-1..1 with j = next() mod (i+1).  pi is HOST [T].
+ * Pure host code.
+ */
+int colbandit_permutation(uint64_t seed, int64_t query_index, int T, int32_t *pi);
+
+/*
+ * Radius pre-factor per unit sigma_hat after n revealed cells (Eq. (7), c = 1,
+ * natural log, rho_n of Appendix A): alpha_ef*T*sqrt(2 ln(N T/delta)/n)*sqrt(rho_n),
+ * +inf for n <= 1.  Pure host code, double precision; the kernels receive its value
+ * rounded to float.
+ */
+double colbandit_radius_prefactor(float alpha_ef, float delta, int T, int64_t N, int n);
+
+/*
+ * Checks the doc_offsets preconditions on the device, synchronises the stream and
+ * returns COLBANDIT_OK or COLBANDIT_ERR_BAD_OFFSETS.  `workspace` needs 256 bytes.
+ */
+int colbandit_validate_offsets(const int64_t *doc_offsets, int64_t N, int64_t total_tokens,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* Static description of an error code. */
+const char *colbandit_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COLBANDIT_H */

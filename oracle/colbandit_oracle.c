@@ -195,7 +195,10 @@ int oracle_bounds(const double *vals, int n, int T, double a, double b,
         sigma = sqrt(ss / (double)(n - 1));
     }
     double r = oracle_radius(alpha, T, sigma, N, delta, n);
-    double shat = (double)T * mu;
+    /* n = T: the row is fully observed, the estimator IS the sum (Appendix A: the
+     * radius collapses entirely); taking it from the sum keeps rounding of
+     * T*(sum/T) from opening a one-ulp gap between LCB and UCB. */
+    double shat = (n == T) ? sum : (double)T * mu;
     double lcb = shat - r, ucb = shat + r;
     if (lbh > lcb) lcb = lbh;      /* max(LB_hard, S_hat - r) */
     if (ubh < ucb) ucb = ubh;      /* min(UB_hard, S_hat + r) */
