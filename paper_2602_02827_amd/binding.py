@@ -1,0 +1,232 @@
+"""ctypes binding of libcolbandit.so: argument marshalling only.
+
+Every step of the scoring path runs in the library's HIP kernels; torch is used here for
+device memory (inputs, outputs, workspace) and for the current stream handle.  There is no
+fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcolbandit.so")
+
+F32, BF16 = 0, 1
+MAX_ROUNDS = 64
+
+EXPORTS = [
+    "colbandit_full_maxsim", "colbandit_topk", "colbandit_workspace_bytes",
+    "colbandit_trace_bytes", "colbandit_permutation", "colbandit_radius_prefactor",
+    "colbandit_validate_offsets", "colbandit_strerror",
+]
+
+
+class ColbanditOpts(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int), ("a", ctypes.c_float), ("b", ctypes.c_float),
+                ("pi", ctypes.c_void_p), ("trace", ctypes.c_void_p),
+                ("trace_bytes", ctypes.c_size_t), ("force_gather", ctypes.c_int)]
+
+
+class ColbanditStats(ctypes.Structure):
+    _fields_ = [("rounds", ctypes.c_int32), ("survivors", ctypes.c_int32 * (MAX_ROUNDS + 2)),
+                ("cells_elim", ctypes.c_int64), ("cells_rescore", ctypes.c_int64),
+                ("cells_unique", ctypes.c_int64), ("ms_total", ctypes.c_float)]
+
+
+class ColbanditError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def lib():
+    """Loads the built library; raises if it is missing (build it with build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not built: run `python -m paper_2602_02827_amd.build` "
+                "(or __graft_entry__.build()) first")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, i64, sz, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float
+        L.colbandit_full_maxsim.restype = i
+        L.colbandit_full_maxsim.argtypes = [vp, i, i, i, i, vp, vp, i64, i64, i, vp, vp, vp, vp,
+                                            vp, sz, vp]
+        L.colbandit_topk.restype = i
+        L.colbandit_topk.argtypes = [vp, i, i, i, i, vp, vp, i64, i64, i, f, f, i, ctypes.c_uint64,
+                                     ctypes.POINTER(ColbanditOpts), vp, vp,
+                                     ctypes.POINTER(ColbanditStats), vp, sz, vp]
+        L.colbandit_workspace_bytes.restype = sz
+        L.colbandit_workspace_bytes.argtypes = [i, i, i, i64, i64, i, i]
+        L.colbandit_trace_bytes.restype = sz
+        L.colbandit_trace_bytes.argtypes = [i, i, i, i64]
+        L.colbandit_permutation.restype = i
+        L.colbandit_permutation.argtypes = [ctypes.c_uint64, i64, i, vp]
+        L.colbandit_radius_prefactor.restype = ctypes.c_double
+        L.colbandit_radius_prefactor.argtypes = [f, f, i, i64, i]
+        L.colbandit_validate_offsets.restype = i
+        L.colbandit_validate_offsets.argtypes = [vp, i64, i64, vp, sz, vp]
+        L.colbandit_strerror.restype = ctypes.c_char_p
+        L.colbandit_strerror.argtypes = [i]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().colbandit_strerror(int(code)).decode()
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError("Q / doc_tokens must be float32 or bfloat16")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _shapes(Q, docs, offsets):
+    if Q.dim() == 2:
+        Q = Q.unsqueeze(0)
+    assert Q.is_contiguous() and docs.is_contiguous() and offsets.is_contiguous()
+    assert offsets.dtype == torch.int64 and Q.dtype == docs.dtype and Q.shape[2] == docs.shape[1]
+    nq, T, d = Q.shape
+    return Q, nq, T, d, int(offsets.shape[0] - 1), int(docs.shape[0])
+
+
+def colbandit_workspace_bytes(nq, T, d, N, total_tokens, K=0, M=0) -> int:
+    return int(lib().colbandit_workspace_bytes(nq, T, d, N, total_tokens, K, M))
+
+
+def colbandit_trace_bytes(nq, T, B, N) -> int:
+    return int(lib().colbandit_trace_bytes(nq, T, B, N))
+
+
+def colbandit_permutation(seed: int, query_index: int, T: int) -> np.ndarray:
+    pi = np.empty(T, dtype=np.int32)
+    rc = lib().colbandit_permutation(ctypes.c_uint64(seed & (2**64 - 1)), query_index, T,
+                                     pi.ctypes.data_as(ctypes.c_void_p))
+    if rc:
+        raise ColbanditError(rc, "colbandit_permutation")
+    return pi
+
+
+def colbandit_radius_prefactor(alpha_ef, delta, T, N, n) -> float:
+    return float(lib().colbandit_radius_prefactor(alpha_ef, delta, T, N, n))
+
+
+def new_workspace(nq, T, d, N, total_tokens, device="cuda") -> torch.Tensor:
+    return torch.empty(colbandit_workspace_bytes(nq, T, d, N, total_tokens), dtype=torch.uint8,
+                       device=device)
+
+
+def colbandit_validate_offsets(offsets: torch.Tensor, total_tokens: int, workspace=None) -> int:
+    ws = workspace if workspace is not None else torch.empty(256, dtype=torch.uint8,
+                                                             device=offsets.device)
+    return int(lib().colbandit_validate_offsets(_ptr(offsets), offsets.shape[0] - 1, total_tokens,
+                                                _ptr(ws), ws.numel(), _stream()))
+
+
+def colbandit_full_maxsim(Q, docs, offsets, K=0, want_scores=True, want_cells=False,
+                          workspace=None, out=None):
+    """Exhaustive scoring.  Returns dict(scores [nq,N] | None, topk_ids, topk_scores, cells)."""
+    Q, nq, T, d, N, total = _shapes(Q, docs, offsets)
+    dev = docs.device
+    ws = workspace if workspace is not None else new_workspace(nq, T, d, N, total, dev)
+    o = out or {}
+    scores = o.get("scores")
+    if scores is None and (want_scores or K == 0):
+        scores = torch.empty((nq, N), dtype=torch.float32, device=dev)
+    ids = sc = None
+    if K > 0:
+        ids = o.get("topk_ids") if o.get("topk_ids") is not None else \
+            torch.empty((nq, K), dtype=torch.int64, device=dev)
+        sc = o.get("topk_scores") if o.get("topk_scores") is not None else \
+            torch.empty((nq, K), dtype=torch.float32, device=dev)
+    cells = torch.empty((nq, N, T), dtype=torch.float32, device=dev) if want_cells else None
+    rc = lib().colbandit_full_maxsim(_ptr(Q), nq, T, d, _dt(Q), _ptr(docs), _ptr(offsets), N, total,
+                                     K, _ptr(scores), _ptr(ids), _ptr(sc), _ptr(cells), _ptr(ws),
+                                     ws.numel(), _stream())
+    if rc:
+        raise ColbanditError(rc, "colbandit_full_maxsim")
+    return {"scores": scores, "topk_ids": ids, "topk_scores": sc, "cells": cells}
+
+
+@dataclass
+class Trace:
+    count: np.ndarray    # [R+1, nq]
+    tau: np.ndarray      # [R, nq]
+    lcb: np.ndarray      # [R, nq, N]
+    ucb: np.ndarray
+    alive: np.ndarray    # bool
+
+
+def _parse_trace(buf: torch.Tensor, nq, T, B, N) -> Trace:
+    R = (T + B - 1) // B
+    raw = buf.cpu().numpy()
+    al = lambda x: (x + 255) // 256 * 256
+    o = 0
+    count = raw[o:o + 4 * (R + 1) * nq].view(np.int32).reshape(R + 1, nq).copy(); o += al(4 * (R + 1) * nq)
+    tau = raw[o:o + 4 * R * nq].view(np.float32).reshape(R, nq).copy(); o += al(4 * R * nq)
+    lcb = raw[o:o + 4 * R * nq * N].view(np.float32).reshape(R, nq, N).copy(); o += al(4 * R * nq * N)
+    ucb = raw[o:o + 4 * R * nq * N].view(np.float32).reshape(R, nq, N).copy(); o += al(4 * R * nq * N)
+    alive = raw[o:o + R * nq * N].reshape(R, nq, N).astype(bool)
+    return Trace(count, tau, lcb, ucb, alive)
+
+
+def colbandit_topk(Q, docs, offsets, K, alpha_ef=0.2, delta=0.01, M=5, seed=0, B=0, a=0.0, b=0.0,
+                   pi=None, trace=False, force_gather=False, want_stats=True, workspace=None,
+                   out=None):
+    """Col-Bandit top-K.  Returns dict(topk_ids, topk_scores, stats (list of dict) | None,
+    trace (Trace) | None).  `pi`: optional int32 device tensor [nq,T]."""
+    Q, nq, T, d, N, total = _shapes(Q, docs, offsets)
+    dev = docs.device
+    ws = workspace if workspace is not None else new_workspace(nq, T, d, N, total, dev)
+    o = out or {}
+    ids = o.get("topk_ids") if o.get("topk_ids") is not None else \
+        torch.empty((nq, K), dtype=torch.int64, device=dev)
+    sc = o.get("topk_scores") if o.get("topk_scores") is not None else \
+        torch.empty((nq, K), dtype=torch.float32, device=dev)
+    opts = ColbanditOpts(B=B, a=a, b=b, pi=None, trace=None, trace_bytes=0,
+                         force_gather=1 if force_gather else 0)
+    tbuf = None
+    Beff = B if B > 0 else 4
+    if pi is not None:
+        assert pi.dtype == torch.int32 and pi.is_contiguous() and tuple(pi.shape) == (nq, T)
+        opts.pi = pi.data_ptr()
+    if trace:
+        tbuf = torch.empty(colbandit_trace_bytes(nq, T, Beff, N), dtype=torch.uint8, device=dev)
+        opts.trace = tbuf.data_ptr()
+        opts.trace_bytes = tbuf.numel()
+    stats = (ColbanditStats * nq)() if want_stats else None
+    rc = lib().colbandit_topk(_ptr(Q), nq, T, d, _dt(Q), _ptr(docs), _ptr(offsets), N, total, K,
+                              alpha_ef, delta, M, ctypes.c_uint64(seed & (2**64 - 1)),
+                              ctypes.byref(opts), _ptr(ids), _ptr(sc), stats, _ptr(ws), ws.numel(),
+                              _stream())
+    if rc:
+        raise ColbanditError(rc, "colbandit_topk")
+    st = None
+    if stats is not None:
+        st = [{"rounds": s.rounds, "survivors": list(s.survivors[: s.rounds + 1]),
+               "cells_elim": s.cells_elim, "cells_rescore": s.cells_rescore,
+               "cells_unique": s.cells_unique, "ms_total": s.ms_total} for s in stats]
+    tr = None
+    if trace:
+        torch.cuda.synchronize()
+        tr = _parse_trace(tbuf, nq, T, Beff, N)
+    return {"topk_ids": ids, "topk_scores": sc, "stats": st, "trace": tr}

@@ -1,0 +1,332 @@
+// C-ABI of the library: argument validation, workspace carving and the host-side
+// sequencing of the kernels.  No device arithmetic lives here.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "../../include/colbandit.h"
+#include "cb_launch.h"
+
+using namespace cb;
+
+namespace {
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Token chunk owned by one workgroup of the dense kernel.
+constexpr int kChunkTokens = 4096;
+
+struct Layout {
+    size_t ctl, list0, list1, sum, m2, rescored, scores, cnt_hist, tau_hist, pi, chunk_doc, flag,
+        total;
+};
+
+Layout make_layout(int nq, int T, int64_t N, int64_t total_tokens) {
+    Layout L{};
+    size_t o = 0;
+    const size_t qn = (size_t)nq * (size_t)N;
+    auto take = [&](size_t bytes) {
+        const size_t at = o;
+        o = align_up(o + bytes);
+        return at;
+    };
+    L.ctl = take(sizeof(QueryCtl) * (size_t)nq);
+    L.list0 = take(4 * qn);
+    L.list1 = take(4 * qn);
+    L.sum = take(4 * qn);
+    L.m2 = take(4 * qn);
+    L.rescored = take(4 * qn);
+    L.scores = take(4 * qn);
+    L.cnt_hist = take(4 * (size_t)(COLBANDIT_MAX_ROUNDS + 2) * nq);
+    L.tau_hist = take(4 * (size_t)(COLBANDIT_MAX_ROUNDS + 2) * nq);
+    L.pi = take(4 * (size_t)nq * T);
+    L.chunk_doc = take(4 * (size_t)(total_tokens / kChunkTokens + 16));
+    L.flag = take(256);
+    L.total = o;
+    return L;
+}
+
+Work carve(void* ws, const Layout& L) {
+    char* b = (char*)ws;
+    Work W{};
+    W.ctl = (QueryCtl*)(b + L.ctl);
+    W.list[0] = (int32_t*)(b + L.list0);
+    W.list[1] = (int32_t*)(b + L.list1);
+    W.sum = (float*)(b + L.sum);
+    W.m2 = (float*)(b + L.m2);
+    W.rescored = (float*)(b + L.rescored);
+    W.scores = (float*)(b + L.scores);
+    W.cnt_hist = (int32_t*)(b + L.cnt_hist);
+    W.tau_hist = (float*)(b + L.tau_hist);
+    W.pi = (int32_t*)(b + L.pi);
+    W.chunk_doc = (int32_t*)(b + L.chunk_doc);
+    W.flag = (int*)(b + L.flag);
+    return W;
+}
+
+int check_shapes(const void* Q, int nq, int T, int d, int dt, const void* docs,
+                 const int64_t* off, int64_t N, int64_t total) {
+    if (!Q || !docs || !off) return COLBANDIT_ERR_NULL;
+    if (nq < 1 || T < 1 || d < 1 || N < 1 || total < N) return COLBANDIT_ERR_SHAPE;
+    if (dt != COLBANDIT_F32 && dt != COLBANDIT_BF16) return COLBANDIT_ERR_SHAPE;
+    if (N > 0x7fffffff - 1024 || nq > 65535) return COLBANDIT_ERR_UNSUPPORTED;
+    if (d != 64 && d != 128) return COLBANDIT_ERR_UNSUPPORTED;
+    if (T > (dt == COLBANDIT_BF16 ? COLBANDIT_MAX_T : 64)) return COLBANDIT_ERR_UNSUPPORTED;
+    if (((uintptr_t)Q & 15) || ((uintptr_t)docs & 15) || ((uintptr_t)off & 7))
+        return COLBANDIT_ERR_ALIGNMENT;
+    return COLBANDIT_OK;
+}
+
+int check_workspace(const void* ws, size_t bytes, size_t need) {
+    if (!ws) return COLBANDIT_ERR_NULL;
+    if ((uintptr_t)ws & 255) return COLBANDIT_ERR_ALIGNMENT;
+    if (bytes < need) return COLBANDIT_ERR_WORKSPACE;
+    return COLBANDIT_OK;
+}
+
+double rho_n(int n, int T) {
+    // finite-population correction, Appendix A
+    if (2 * n <= T) return 1.0 - (double)(n - 1) / (double)T;
+    return (1.0 - (double)n / (double)T) * (1.0 + 1.0 / (double)n);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* colbandit_strerror(int code) {
+    switch (code) {
+        case COLBANDIT_OK: return "ok";
+        case COLBANDIT_ERR_NULL: return "a required pointer is NULL";
+        case COLBANDIT_ERR_SHAPE: return "invalid size (n_queries, T, d, N, total_tokens, K or dtype)";
+        case COLBANDIT_ERR_KNOB: return "knob out of range (alpha_ef, delta, M, B or support [a,b])";
+        case COLBANDIT_ERR_UNSUPPORTED: return "request outside what this build's kernels cover";
+        case COLBANDIT_ERR_WORKSPACE: return "workspace or trace buffer too small";
+        case COLBANDIT_ERR_ALIGNMENT: return "pointer not aligned as required";
+        case COLBANDIT_ERR_HIP: return "HIP runtime error";
+        case COLBANDIT_ERR_BAD_OFFSETS: return "doc_offsets violates its preconditions";
+        default: return "unknown error code";
+    }
+}
+
+int colbandit_permutation(uint64_t seed, int64_t query_index, int T, int32_t* pi) {
+    if (!pi) return COLBANDIT_ERR_NULL;
+    if (T < 1 || query_index < 0) return COLBANDIT_ERR_SHAPE;
+    uint64_t s = seed + ((uint64_t)query_index + 1ull) * 0x9E3779B97F4A7C15ull;
+    for (int t = 0; t < T; ++t) pi[t] = t;
+    for (int i = T - 1; i >= 1; --i) {
+        s += 0x9E3779B97F4A7C15ull;
+        uint64_t z = s;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        const int j = (int)(z % (uint64_t)(i + 1));
+        const int32_t tmp = pi[i];
+        pi[i] = pi[j];
+        pi[j] = tmp;
+    }
+    return COLBANDIT_OK;
+}
+
+double colbandit_radius_prefactor(float alpha_ef, float delta, int T, int64_t N, int n) {
+    if (n <= 1) return INFINITY;
+    const double lg = log((double)N * (double)T / (double)delta);
+    return (double)alpha_ef * (double)T * sqrt(2.0 * lg / (double)n) * sqrt(rho_n(n, T));
+}
+
+size_t colbandit_trace_bytes(int n_queries, int T, int B, int64_t N) {
+    if (n_queries < 1 || T < 1 || B < 1 || N < 1) return 0;
+    const size_t R = (size_t)((T + B - 1) / B), nq = (size_t)n_queries;
+    return align_up(4 * (R + 1) * nq) + align_up(4 * R * nq) + 2 * align_up(4 * R * nq * (size_t)N) +
+           align_up(R * nq * (size_t)N);
+}
+
+size_t colbandit_workspace_bytes(int n_queries, int T, int d, int64_t N, int64_t total_tokens,
+                                 int K, int M) {
+    (void)d; (void)K; (void)M;
+    if (n_queries < 1 || T < 1 || N < 1 || total_tokens < N) return 0;
+    return make_layout(n_queries, T, N, total_tokens).total;
+}
+
+int colbandit_validate_offsets(const int64_t* doc_offsets, int64_t N, int64_t total_tokens,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+    if (!doc_offsets) return COLBANDIT_ERR_NULL;
+    if (N < 1 || total_tokens < N) return COLBANDIT_ERR_SHAPE;
+    int rc = check_workspace(workspace, workspace_bytes, 256);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    int* flag = (int*)workspace;
+    if (launch_validate_offsets(doc_offsets, N, total_tokens, flag, st) != hipSuccess)
+        return COLBANDIT_ERR_HIP;
+    int h = 0;
+    if (hipMemcpyAsync(&h, flag, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return COLBANDIT_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return COLBANDIT_ERR_HIP;
+    return h ? COLBANDIT_ERR_BAD_OFFSETS : COLBANDIT_OK;
+}
+
+int colbandit_full_maxsim(const void* Q, int n_queries, int T, int d, colbandit_dtype dt,
+                          const void* doc_tokens, const int64_t* doc_offsets, int64_t N,
+                          int64_t total_tokens, int K, float* scores, int64_t* topk_ids,
+                          float* topk_scores, float* cells, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+    int rc = check_shapes(Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens);
+    if (rc) return rc;
+    if (K < 0 || K > N) return COLBANDIT_ERR_SHAPE;
+    if (K > COLBANDIT_MAX_K) return COLBANDIT_ERR_UNSUPPORTED;
+    if (K == 0 && !scores) return COLBANDIT_ERR_NULL;
+    if (K > 0 && (!topk_ids || !topk_scores)) return COLBANDIT_ERR_NULL;
+    const Layout L = make_layout(n_queries, T, N, total_tokens);
+    rc = check_workspace(workspace, workspace_bytes, L.total);
+    if (rc) return rc;
+
+    const Work W = carve(workspace, L);
+    const Problem P{Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens};
+    hipStream_t st = (hipStream_t)stream;
+    float* out = scores ? scores : W.scores;
+
+    hipError_t e;
+    if (dense_supported(P)) {
+        int n_chunks = 0;
+        e = launch_dense_prepare(P, W, kChunkTokens, &n_chunks, st);
+        if (e == hipSuccess) e = launch_dense_score(P, W, kChunkTokens, n_chunks, out, cells, st);
+    } else {
+        e = launch_gather_score(P, W, false, out, cells, st);
+    }
+    if (e == hipSuccess && K > 0) e = launch_topk(P, W, false, out, K, topk_ids, topk_scores, st);
+    return e == hipSuccess ? COLBANDIT_OK : COLBANDIT_ERR_HIP;
+}
+
+int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype dt,
+                   const void* doc_tokens, const int64_t* doc_offsets, int64_t N,
+                   int64_t total_tokens, int K, float alpha_ef, float delta, int M, uint64_t seed,
+                   const colbandit_opts* opts, int64_t* topk_ids, float* topk_scores,
+                   colbandit_stats* stats, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+    int rc = check_shapes(Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens);
+    if (rc) return rc;
+    if (!topk_ids || !topk_scores) return COLBANDIT_ERR_NULL;
+    if (K < 1 || K > N) return COLBANDIT_ERR_SHAPE;
+    if (K > COLBANDIT_MAX_K) return COLBANDIT_ERR_UNSUPPORTED;
+    if (!(alpha_ef > 0.f) || !(alpha_ef <= 1.f) || !(delta > 0.f) || !(delta < 1.f) || M < 0)
+        return COLBANDIT_ERR_KNOB;
+    Knobs kn{K, M, 4, -1.f, 1.f};
+    const int32_t* user_pi = nullptr;
+    void* trace = nullptr;
+    size_t trace_bytes = 0;
+    bool force_gather = false;
+    if (opts) {
+        if (opts->B < 0) return COLBANDIT_ERR_KNOB;
+        if (opts->B > 0) kn.B = opts->B;
+        if (!(opts->a == 0.f && opts->b == 0.f)) {
+            if (!(opts->a < opts->b)) return COLBANDIT_ERR_KNOB;
+            kn.a = opts->a;
+            kn.b = opts->b;
+        }
+        user_pi = opts->pi;
+        trace = opts->trace;
+        trace_bytes = opts->trace_bytes;
+        force_gather = opts->force_gather != 0;
+    }
+    if (kn.B > COLBANDIT_MAX_B) return COLBANDIT_ERR_UNSUPPORTED;
+    const int R = (T + kn.B - 1) / kn.B;
+    if (R > COLBANDIT_MAX_ROUNDS) return COLBANDIT_ERR_UNSUPPORTED;
+    const Layout L = make_layout(n_queries, T, N, total_tokens);
+    rc = check_workspace(workspace, workspace_bytes, L.total);
+    if (rc) return rc;
+
+    Trace tr{};
+    if (trace) {
+        if ((uintptr_t)trace & 255) return COLBANDIT_ERR_ALIGNMENT;
+        if (trace_bytes < colbandit_trace_bytes(n_queries, T, kn.B, N)) return COLBANDIT_ERR_WORKSPACE;
+        char* b = (char*)trace;
+        const size_t nq = (size_t)n_queries, Rn = (size_t)R;
+        tr.count = (int32_t*)b;
+        b += align_up(4 * (Rn + 1) * nq);
+        tr.tau = (float*)b;
+        b += align_up(4 * Rn * nq);
+        tr.lcb = (float*)b;
+        b += align_up(4 * Rn * nq * (size_t)N);
+        tr.ucb = (float*)b;
+        b += align_up(4 * Rn * nq * (size_t)N);
+        tr.alive = (uint8_t*)b;
+    }
+
+    const Work W = carve(workspace, L);
+    const Problem P{Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens};
+    hipStream_t st = (hipStream_t)stream;
+
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (stats) {
+        if (hipEventCreate(&ev0) != hipSuccess || hipEventCreate(&ev1) != hipSuccess)
+            return COLBANDIT_ERR_HIP;
+        (void)hipEventRecord(ev0, st);
+    }
+
+    hipError_t e = launch_init(P, W, kn, R, seed, user_pi, tr, st);
+    const bool loop = N > (int64_t)K + M;    // |A_1| > K + M, else the loop body never runs
+    const bool dense = dense_supported(P) && !force_gather;
+    int n_chunks = 0;
+    if (e == hipSuccess && loop && dense) e = launch_dense_prepare(P, W, kChunkTokens, &n_chunks, st);
+    for (int r = 1; e == hipSuccess && loop && r <= R; ++r) {
+        RevealRound rr{};
+        rr.r = r;
+        rr.lo = (r - 1) * kn.B;
+        rr.nb = (r * kn.B < T ? r * kn.B : T) - rr.lo;
+        rr.n_prev = rr.lo;
+        rr.n = rr.lo + rr.nb;
+        const double kap = colbandit_radius_prefactor(alpha_ef, delta, T, N, rr.n);
+        rr.kappa = isinf(kap) ? 0.f : (float)kap;   // unused by the kernels when n <= 1
+        if (r == 1 && dense) {
+            int G = 1;
+            while (G < rr.nb) G <<= 1;
+            e = launch_dense_reveal(P, W, kChunkTokens, n_chunks, rr, G, st);
+        } else {
+            e = launch_gather_reveal(P, W, rr, st);
+        }
+        if (e == hipSuccess) e = launch_select_prune(P, W, kn, rr, tr, st);
+    }
+    if (e == hipSuccess) e = launch_gather_score(P, W, true, W.rescored, nullptr, st);
+    if (e == hipSuccess) e = launch_topk(P, W, true, W.rescored, K, topk_ids, topk_scores, st);
+    if (e != hipSuccess) {
+        if (stats) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); }
+        return COLBANDIT_ERR_HIP;
+    }
+    if (!stats) return COLBANDIT_OK;
+
+    // statistics: the per-round survivor counts come back in one copy after the last kernel
+    (void)hipEventRecord(ev1, st);
+    const size_t nh = (size_t)(R + 1) * n_queries;
+    int32_t* hist = (int32_t*)malloc(sizeof(int32_t) * nh);
+    if (!hist) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); return COLBANDIT_ERR_HIP; }
+    hipError_t ce = hipMemcpyAsync(hist, W.cnt_hist, sizeof(int32_t) * nh, hipMemcpyDeviceToHost, st);
+    if (ce == hipSuccess) ce = hipStreamSynchronize(st);
+    float ms = 0.f;
+    if (ce == hipSuccess) (void)hipEventElapsedTime(&ms, ev0, ev1);
+    (void)hipEventDestroy(ev0);
+    (void)hipEventDestroy(ev1);
+    if (ce != hipSuccess) { free(hist); return COLBANDIT_ERR_HIP; }
+    for (int q = 0; q < n_queries; ++q) {
+        colbandit_stats& s = stats[q];
+        memset(&s, 0, sizeof(s));
+        s.survivors[0] = (int32_t)N;
+        int64_t count = N;
+        int n = 0, r = 0;
+        while (loop && count > (int64_t)K + M && r * kn.B < T) {   // the loop condition of Algorithm 1
+            const int lo = r * kn.B, hi = (r + 1) * kn.B < T ? (r + 1) * kn.B : T;
+            s.cells_elim += (int64_t)(hi - lo) * count;
+            n = hi;
+            ++r;
+            count = hist[(size_t)r * n_queries + q];
+            s.survivors[r] = (int32_t)count;
+        }
+        s.rounds = r;
+        s.cells_rescore = (int64_t)T * count;
+        s.cells_unique = s.cells_elim + (int64_t)(T - n) * count;
+        s.ms_total = ms;
+    }
+    free(hist);
+    return COLBANDIT_OK;
+}
+
+}  // extern "C"

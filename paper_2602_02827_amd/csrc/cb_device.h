@@ -9,9 +9,11 @@ namespace cb {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-struct bf16_tag {};
-struct f32_tag {};
+// `wide`: up to 8 column tiles (T <= 128) fit the register file; fp32 stops at 4.
+struct bf16_tag { static constexpr bool wide = true; };
+struct f32_tag { static constexpr bool wide = false; };
 
 // Per-query round control, resident in the workspace.  `implicit` means the active set
 // is still all N documents in index order (no list has been written yet).
@@ -163,7 +165,7 @@ __device__ __forceinline__ void interval(float S, float M2, int n, int T, float 
 
 // Order-preserving map float -> uint32 (larger float, larger key).
 __device__ __forceinline__ uint32_t float_key(float f) {
-    uint32_t u = __float_as_uint(f);
+    uint32_t u = __float_as_uint(f + 0.0f);   // -0 and +0 share a key
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 __device__ __forceinline__ float key_float(uint32_t k) {

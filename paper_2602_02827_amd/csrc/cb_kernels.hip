@@ -1,0 +1,592 @@
+// Gather-reveal / rescore kernel, bound-driven selection and pruning, top-K, and the
+// small control kernels.  gfx950 only.
+#include "cb_launch.h"
+
+namespace cb {
+
+// =====================================================================================
+// init: per-query control, reveal permutations, history and trace fill
+// =====================================================================================
+__device__ __forceinline__ uint64_t splitmix64_next(uint64_t& s) {
+    s += 0x9E3779B97F4A7C15ull;
+    uint64_t z = s;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__global__ void k_init(QueryCtl* ctl, int32_t* pi, const int32_t* user_pi, int32_t* cnt_hist,
+                       float* tau_hist, int nq, int T, int R, int64_t N, int KM, uint64_t seed,
+                       int32_t* tr_count, float* tr_tau) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= nq) return;
+    QueryCtl c;
+    c.count = (int)N;
+    c.cur = 0;
+    c.implicit = 1;
+    c.active = N > (int64_t)KM;
+    ctl[q] = c;
+    for (int r = 0; r <= R; ++r) {
+        cnt_hist[r * nq + q] = (int)N;
+        if (tr_count) tr_count[r * nq + q] = (int)N;
+    }
+    for (int r = 0; r < R; ++r) {
+        tau_hist[r * nq + q] = __builtin_nanf("");
+        if (tr_tau) tr_tau[r * nq + q] = __builtin_nanf("");
+    }
+    int32_t* p = pi + (size_t)q * T;
+    if (user_pi) {
+        for (int t = 0; t < T; ++t) p[t] = user_pi[(size_t)q * T + t];
+    } else {
+        // Fisher-Yates driven by SplitMix64 (Sec. 4.2: one seeded uniform permutation per query)
+        uint64_t s = seed + ((uint64_t)q + 1ull) * 0x9E3779B97F4A7C15ull;
+        for (int t = 0; t < T; ++t) p[t] = t;
+        for (int i = T - 1; i >= 1; --i) {
+            const int j = (int)(splitmix64_next(s) % (uint64_t)(i + 1));
+            const int32_t tmp = p[i];
+            p[i] = p[j];
+            p[j] = tmp;
+        }
+    }
+}
+
+__global__ void k_fill_f32(float* p, size_t n, float v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (size_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+__global__ void k_fill_u8(uint8_t* p, size_t n, uint8_t v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (size_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+hipError_t launch_init(const Problem& P, const Work& W, const Knobs& kn, int R, uint64_t seed,
+                       const int32_t* user_pi, const Trace& tr, hipStream_t st) {
+    k_init<<<(P.nq + 63) / 64, 64, 0, st>>>(W.ctl, W.pi, user_pi, W.cnt_hist, W.tau_hist, P.nq,
+                                            P.T, R, P.N, kn.K + kn.M, seed, tr.count, tr.tau);
+    if (tr.lcb) {
+        const size_t n = (size_t)R * P.nq * P.N;
+        const int g = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+        k_fill_f32<<<g, 256, 0, st>>>(tr.lcb, n, __builtin_nanf(""));
+        k_fill_f32<<<g, 256, 0, st>>>(tr.ucb, n, __builtin_nanf(""));
+        k_fill_u8<<<g, 256, 0, st>>>(tr.alive, n, 0);
+    }
+    return hipGetLastError();
+}
+
+// =====================================================================================
+// gather kernel: one wavefront per (query, document) pair.
+//
+// The wavefront keeps the query rows it needs as B operands in registers, streams the
+// document's tokens from global memory in blocks of 16 rows (A operand, rows past the
+// end of the document repeat its last token, which cannot change a max), runs the MFMA
+// chain over d and folds the 16x16 result into a running per-column maximum.
+//   REVEAL: one 16-column tile, column c < nb is query token pi[lo+c]; the epilogue
+//           merges the batch into the pair's (sum, M2).       [Algorithm 1, reveal step]
+//   score : TQ tiles = all T tokens; the epilogue is the row sum. [Eq. (2); rescore step]
+// =====================================================================================
+struct GatherArgs {
+    const void* Q;
+    const void* docs;
+    const int64_t* off;
+    int64_t N, total;
+    int T;
+    const QueryCtl* ctl;      // nullptr: every query scores all N documents
+    const int32_t* list0;
+    const int32_t* list1;
+    // reveal
+    const int32_t* pi;
+    int lo, nb, n_prev;
+    float* sum;
+    float* m2;
+    // score
+    float* out;
+    float* cells;
+};
+
+template <typename Tag, int D, int TQ, bool REVEAL>
+__global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
+    using F = Frag<Tag, D>;
+    const int q = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int col = lane & 15;
+    const int kg = lane >> 4;
+    const size_t row_bytes = (size_t)D * F::ELEM_BYTES;
+
+    int count = (int)A.N;
+    const int32_t* list = nullptr;
+    if (A.ctl) {
+        const QueryCtl c = A.ctl[q];
+        if (REVEAL && !c.active) return;
+        count = c.count;
+        if (!c.implicit) list = (c.cur ? A.list1 : A.list0) + (size_t)q * A.N;
+    }
+    const int first = blockIdx.x * 4 + wave;
+    if (first >= count) return;
+
+    // query rows -> B fragments
+    F bq[TQ];
+    const char* Qq = (const char*)A.Q + (size_t)q * A.T * row_bytes;
+#pragma unroll
+    for (int tt = 0; tt < TQ; ++tt) {
+        int trow;
+        if (REVEAL) {
+            trow = A.pi[(size_t)q * A.T + A.lo + (col < A.nb ? col : 0)];
+        } else {
+            const int t = tt * 16 + col;
+            trow = t < A.T ? t : 0;
+        }
+        bq[tt].load(Qq + (size_t)trow * row_bytes, kg);
+    }
+
+    const int stride = gridDim.x * 4;
+    for (int k = first; k < count; k += stride) {
+        const int id = list ? list[k] : k;
+        int64_t o0 = A.off[id], o1 = A.off[id + 1];
+        o0 = o0 < 0 ? 0 : (o0 > A.total ? A.total : o0);
+        o1 = o1 < o0 ? o0 : (o1 > A.total ? A.total : o1);
+
+        float h[TQ];
+#pragma unroll
+        for (int tt = 0; tt < TQ; ++tt) h[tt] = -__builtin_inff();
+
+        for (int64_t r0 = o0; r0 < o1; r0 += 16) {
+            int64_t row = r0 + col;
+            row = row < o1 ? row : o1 - 1;
+            F a;
+            a.load((const char*)A.docs + (size_t)row * row_bytes, kg);
+#pragma unroll
+            for (int tt = 0; tt < TQ; ++tt) {
+                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+                F::mma(acc, a, bq[tt]);
+                h[tt] = fmaxf(h[tt], max4(acc));
+            }
+        }
+#pragma unroll
+        for (int tt = 0; tt < TQ; ++tt) h[tt] = colmax_rows(h[tt]);
+
+        if (REVEAL) {
+            float sb, m2b;
+            batch_stats(h[0], col, A.nb, 16, sb, m2b);
+            if (lane == 0) {
+                const size_t x = (size_t)q * A.N + id;
+                float S = 0.f, M2 = 0.f;
+                if (A.n_prev > 0) {
+                    S = A.sum[x];
+                    M2 = A.m2[x];
+                }
+                merge_stats(S, M2, A.n_prev, sb, m2b, A.nb);
+                A.sum[x] = S;
+                A.m2[x] = M2;
+            }
+        } else {
+            const float s = score_from_colmax<TQ>(h, A.T, col);
+            if (lane == 0) A.out[(size_t)q * A.N + (A.ctl ? k : id)] = s;
+            if (A.cells && lane < 16) {
+#pragma unroll
+                for (int tt = 0; tt < TQ; ++tt) {
+                    const int t = tt * 16 + col;
+                    if (t < A.T) A.cells[((size_t)q * A.N + id) * A.T + t] = h[tt];
+                }
+            }
+        }
+    }
+}
+
+template <typename Tag, int D>
+static hipError_t gather_dispatch(const GatherArgs& A, bool reveal, int nq, int64_t max_count,
+                                  hipStream_t st) {
+    int gx = (int)((max_count + 3) / 4);
+    if (gx > 256) gx = 256;
+    if (gx < 1) gx = 1;
+    const dim3 grid(gx, nq), block(256);
+    if (reveal) {
+        k_gather<Tag, D, 1, true><<<grid, block, 0, st>>>(A);
+    } else {
+        const int tq = (A.T + 15) / 16;
+        if (tq <= 1) k_gather<Tag, D, 1, false><<<grid, block, 0, st>>>(A);
+        else if (tq <= 2) k_gather<Tag, D, 2, false><<<grid, block, 0, st>>>(A);
+        else if (tq <= 4) k_gather<Tag, D, 4, false><<<grid, block, 0, st>>>(A);
+        else if constexpr (Tag::wide) k_gather<Tag, D, 8, false><<<grid, block, 0, st>>>(A);
+        else return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+static void fill_gather_common(GatherArgs& A, const Problem& P, const Work& W) {
+    A.Q = P.Q;
+    A.docs = P.docs;
+    A.off = P.off;
+    A.N = P.N;
+    A.total = P.total;
+    A.T = P.T;
+    A.list0 = W.list[0];
+    A.list1 = W.list[1];
+    A.pi = W.pi;
+    A.sum = W.sum;
+    A.m2 = W.m2;
+}
+
+template <typename Tag>
+static hipError_t gather_by_d(const GatherArgs& A, bool reveal, const Problem& P, hipStream_t st) {
+    if (P.d == 128) return gather_dispatch<Tag, 128>(A, reveal, P.nq, P.N, st);
+    if (P.d == 64) return gather_dispatch<Tag, 64>(A, reveal, P.nq, P.N, st);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_gather_reveal(const Problem& P, const Work& W, const RevealRound& rr,
+                                hipStream_t st) {
+    GatherArgs A{};
+    fill_gather_common(A, P, W);
+    A.ctl = W.ctl;
+    A.lo = rr.lo;
+    A.nb = rr.nb;
+    A.n_prev = rr.n_prev;
+    return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, true, P, st)
+                           : gather_by_d<f32_tag>(A, true, P, st);
+}
+
+hipError_t launch_gather_score(const Problem& P, const Work& W, bool use_ctl, float* out,
+                               float* cells, hipStream_t st) {
+    GatherArgs A{};
+    fill_gather_common(A, P, W);
+    A.ctl = use_ctl ? W.ctl : nullptr;
+    A.out = out;
+    A.cells = cells;
+    return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, false, P, st)
+                           : gather_by_d<f32_tag>(A, false, P, st);
+}
+
+// =====================================================================================
+// block-wide helpers for the one-workgroup-per-query kernels (1024 threads)
+// =====================================================================================
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_WAVES = SEL_THREADS / 64;
+
+// Exclusive scan of v over the block in thread order; returns the thread's offset and the
+// block total.  wtot: LDS int[SEL_WAVES].  Two barriers.
+__device__ __forceinline__ int block_excl_scan(int v, int* wtot, int& total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+    }
+    if (lane == 63) wtot[wave] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < SEL_WAVES; ++w) {
+        const int x = wtot[w];
+        if (w < wave) base += x;
+        tot += x;
+    }
+    __syncthreads();
+    total = tot;
+    return base + incl - v;
+}
+
+// Key of the K-th largest element (1 <= K <= count) of key_of(0..count-1): three radix
+// passes (11+11+10 bits) over the candidates with an LDS histogram each.
+// hist: LDS uint32[2048]; pick: LDS int[2].
+template <class KeyFn>
+__device__ uint32_t block_kth_largest(int count, int K, KeyFn key_of, uint32_t* hist, int* pick) {
+    uint32_t prefix = 0, pmask = 0;
+    int kk = K;
+#pragma unroll 1
+    for (int p = 0; p < 3; ++p) {
+        const int shift = p == 0 ? 21 : (p == 1 ? 10 : 0);
+        const int nbins = p == 2 ? 1024 : 2048;
+        for (int i = threadIdx.x; i < 2048; i += SEL_THREADS) hist[i] = 0;
+        if (threadIdx.x == 0) {
+            pick[0] = 0;
+            pick[1] = 1;
+        }
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < count; idx += SEL_THREADS) {
+            const uint32_t key = key_of(idx);
+            if ((key & pmask) == prefix) atomicAdd(&hist[(key >> shift) & (nbins - 1)], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x < 64) {
+            const int lane = threadIdx.x;
+            const int per = nbins / 64;
+            const int hi = nbins - 1 - lane * per;       // this lane's bins, descending
+            int local = 0;
+            for (int j = 0; j < per; ++j) local += (int)hist[hi - j];
+            int incl = local;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o);
+                if (lane >= o) incl += t;
+            }
+            const int excl = incl - local;
+            if (excl < kk && kk <= incl) {
+                int run = excl;
+                for (int j = 0; j < per; ++j) {
+                    const int c = (int)hist[hi - j];
+                    if (run + c >= kk) {
+                        pick[0] = hi - j;
+                        pick[1] = kk - run;
+                        break;
+                    }
+                    run += c;
+                }
+            }
+        }
+        __syncthreads();
+        prefix |= (uint32_t)pick[0] << shift;
+        pmask |= (uint32_t)(nbins - 1) << shift;
+        kk = pick[1];
+        __syncthreads();
+    }
+    return prefix;
+}
+
+// =====================================================================================
+// threshold + prune: tau_r = K-th largest LCB over the active set, A_{r+1} = {UCB >= tau_r}
+// (Algorithm 1, threshold and elimination steps), one workgroup per query, stable.
+// =====================================================================================
+struct SelArgs {
+    QueryCtl* ctl;
+    int32_t* list0;
+    int32_t* list1;
+    const float* sum;
+    const float* m2;
+    int64_t N;
+    int nq, T, K, KM;
+    int r, n;
+    float kappa, a, b;
+    int32_t* cnt_hist;
+    float* tau_hist;
+    int32_t* tr_count;
+    float* tr_tau;
+    float* tr_lcb;
+    float* tr_ucb;
+    uint8_t* tr_alive;
+};
+
+__global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
+    __shared__ uint32_t hist[2048];
+    __shared__ int pick[2];
+    __shared__ int wtot[SEL_WAVES];
+    const int q = blockIdx.x;
+    const QueryCtl c = A.ctl[q];
+    if (!c.active) {
+        if (threadIdx.x == 0) {
+            A.cnt_hist[A.r * A.nq + q] = c.count;
+            if (A.tr_count) A.tr_count[A.r * A.nq + q] = c.count;
+        }
+        return;
+    }
+    const int count = c.count;
+    const int32_t* in = c.implicit ? nullptr : (c.cur ? A.list1 : A.list0) + (size_t)q * A.N;
+    const int out_sel = c.implicit ? 0 : (c.cur ^ 1);
+    int32_t* out = (out_sel ? A.list1 : A.list0) + (size_t)q * A.N;
+    const float* sum = A.sum + (size_t)q * A.N;
+    const float* m2 = A.m2 + (size_t)q * A.N;
+    const int n = A.n, T = A.T;
+    const float kappa = A.kappa, a = A.a, b = A.b;
+
+    auto key_of = [&](int idx) -> uint32_t {
+        const int id = in ? in[idx] : idx;
+        float lcb, ucb;
+        interval(sum[id], m2[id], n, T, kappa, a, b, lcb, ucb);
+        return float_key(lcb);
+    };
+    const uint32_t tkey = block_kth_largest(count, A.K, key_of, hist, pick);
+    const float tau = key_float(tkey);
+
+    const size_t tro = ((size_t)(A.r - 1) * A.nq + q) * A.N;
+    int base = 0;
+    for (int start = 0; start < count; start += SEL_THREADS) {
+        const int idx = start + threadIdx.x;
+        int id = -1;
+        bool keep = false;
+        if (idx < count) {
+            id = in ? in[idx] : idx;
+            float lcb, ucb;
+            interval(sum[id], m2[id], n, T, kappa, a, b, lcb, ucb);
+            keep = ucb >= tau;
+            if (A.tr_lcb) {
+                A.tr_lcb[tro + id] = lcb;
+                A.tr_ucb[tro + id] = ucb;
+                A.tr_alive[tro + id] = keep ? 1 : 0;
+            }
+        }
+        int total;
+        const int pos = block_excl_scan(keep ? 1 : 0, wtot, total);
+        if (keep) out[base + pos] = id;
+        base += total;
+    }
+    if (threadIdx.x == 0) {
+        QueryCtl nc;
+        nc.count = base;
+        nc.cur = out_sel;
+        nc.implicit = 0;
+        nc.active = base > A.KM;
+        A.ctl[q] = nc;
+        A.cnt_hist[A.r * A.nq + q] = base;
+        A.tau_hist[(A.r - 1) * A.nq + q] = tau;
+        if (A.tr_count) {
+            A.tr_count[A.r * A.nq + q] = base;
+            A.tr_tau[(A.r - 1) * A.nq + q] = tau;
+        }
+    }
+}
+
+hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
+                               const RevealRound& rr, const Trace& tr, hipStream_t st) {
+    SelArgs A{};
+    A.ctl = W.ctl;
+    A.list0 = W.list[0];
+    A.list1 = W.list[1];
+    A.sum = W.sum;
+    A.m2 = W.m2;
+    A.N = P.N;
+    A.nq = P.nq;
+    A.T = P.T;
+    A.K = kn.K;
+    A.KM = kn.K + kn.M;
+    A.r = rr.r;
+    A.n = rr.n;
+    A.kappa = rr.kappa;
+    A.a = kn.a;
+    A.b = kn.b;
+    A.cnt_hist = W.cnt_hist;
+    A.tau_hist = W.tau_hist;
+    A.tr_count = tr.count;
+    A.tr_tau = tr.tau;
+    A.tr_lcb = tr.lcb;
+    A.tr_ucb = tr.ucb;
+    A.tr_alive = tr.alive;
+    k_select_prune<<<P.nq, SEL_THREADS, 0, st>>>(A);
+    return hipGetLastError();
+}
+
+// =====================================================================================
+// top-K by (value descending, document index ascending), one workgroup per query
+// (Eq. (3); final step of Algorithm 1).  Candidates arrive in ascending id order, so
+// ties at the K-th value are resolved towards the lower index by taking them in order.
+// =====================================================================================
+struct TopkArgs {
+    const QueryCtl* ctl;   // nullptr: all N documents, vals indexed by id
+    const int32_t* list0;
+    const int32_t* list1;
+    const float* vals;     // [nq][N]
+    int64_t N;
+    int K;
+    int64_t* out_ids;
+    float* out_scores;
+};
+
+__global__ __launch_bounds__(SEL_THREADS) void k_topk(TopkArgs A) {
+    __shared__ uint32_t hist[2048];
+    __shared__ int pick[2];
+    __shared__ int wtot[SEL_WAVES];
+    __shared__ float cs[1024];
+    __shared__ int ci[1024];
+    const int q = blockIdx.x;
+    int count = (int)A.N;
+    const int32_t* list = nullptr;
+    if (A.ctl) {
+        const QueryCtl c = A.ctl[q];
+        count = c.count;
+        if (!c.implicit) list = (c.cur ? A.list1 : A.list0) + (size_t)q * A.N;
+    }
+    const float* vals = A.vals + (size_t)q * A.N;
+    const int Kq = A.K < count ? A.K : count;
+    if (Kq > 0) {
+        auto key_of = [&](int idx) -> uint32_t { return float_key(vals[idx]); };
+        const uint32_t tkey = block_kth_largest(count, Kq, key_of, hist, pick);
+        // how many are strictly above the K-th value
+        int gt_local = 0;
+        for (int idx = threadIdx.x; idx < count; idx += SEL_THREADS)
+            gt_local += float_key(vals[idx]) > tkey;
+        int n_gt;
+        block_excl_scan(gt_local, wtot, n_gt);
+        const int need_eq = Kq - n_gt;
+        int base_gt = 0, base_eq = 0;
+        for (int start = 0; start < count; start += SEL_THREADS) {
+            const int idx = start + threadIdx.x;
+            bool gt = false, eq = false;
+            float v = 0.f;
+            if (idx < count) {
+                v = vals[idx];
+                const uint32_t key = float_key(v);
+                gt = key > tkey;
+                eq = key == tkey;
+            }
+            int tot;
+            const int pos = block_excl_scan((gt ? 1 : 0) | (eq ? (1 << 16) : 0), wtot, tot);
+            const int pg = base_gt + (pos & 0xffff), pe = base_eq + (pos >> 16);
+            int slot = -1;
+            if (gt) slot = pg;
+            else if (eq && pe < need_eq) slot = n_gt + pe;
+            if (slot >= 0) {
+                cs[slot] = v;
+                ci[slot] = list ? list[idx] : idx;
+            }
+            base_gt += tot & 0xffff;
+            base_eq += tot >> 16;
+        }
+        __syncthreads();
+        if (threadIdx.x < Kq) {
+            const float v = cs[threadIdx.x];
+            const int id = ci[threadIdx.x];
+            int rank = 0;
+            for (int j = 0; j < Kq; ++j) {
+                const float u = cs[j];
+                rank += (u > v) || (u == v && ci[j] < id);
+            }
+            A.out_ids[(size_t)q * A.K + rank] = id;
+            A.out_scores[(size_t)q * A.K + rank] = v;
+        }
+    }
+    for (int k = Kq + threadIdx.x; k < A.K; k += SEL_THREADS) {
+        A.out_ids[(size_t)q * A.K + k] = -1;
+        A.out_scores[(size_t)q * A.K + k] = -__builtin_inff();
+    }
+}
+
+hipError_t launch_topk(const Problem& P, const Work& W, bool use_ctl, const float* vals, int K,
+                       int64_t* out_ids, float* out_scores, hipStream_t st) {
+    TopkArgs A{};
+    A.ctl = use_ctl ? W.ctl : nullptr;
+    A.list0 = W.list[0];
+    A.list1 = W.list[1];
+    A.vals = vals;
+    A.N = P.N;
+    A.K = K;
+    A.out_ids = out_ids;
+    A.out_scores = out_scores;
+    k_topk<<<P.nq, SEL_THREADS, 0, st>>>(A);
+    return hipGetLastError();
+}
+
+// =====================================================================================
+// offsets validation
+// =====================================================================================
+__global__ void k_validate_offsets(const int64_t* off, int64_t N, int64_t total, int* flag) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        bool bad = off[i + 1] <= off[i];
+        if (i == 0) bad = bad || off[0] < 0 || off[N] > total;
+        if (bad) atomicOr(flag, 1);
+    }
+}
+__global__ void k_zero_flag(int* flag) { flag[0] = 0; }
+
+hipError_t launch_validate_offsets(const int64_t* off, int64_t N, int64_t total, int* flag,
+                                   hipStream_t st) {
+    k_zero_flag<<<1, 1, 0, st>>>(flag);
+    int g = (int)((N + 255) / 256);
+    if (g > 2048) g = 2048;
+    k_validate_offsets<<<g, 256, 0, st>>>(off, N, total, flag);
+    return hipGetLastError();
+}
+
+}  // namespace cb

@@ -1,0 +1,87 @@
+// Host-side launch interface between the C-ABI layer and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cb_device.h"
+
+namespace cb {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+struct Problem {
+    const void* Q;
+    int nq, T, d, dt;
+    const void* docs;
+    const int64_t* off;
+    int64_t N, total;
+};
+
+// Views into the caller's workspace (all device pointers).
+struct Work {
+    QueryCtl* ctl;        // [nq]
+    int32_t* list[2];     // [nq][N] each: ids of the active set, ascending
+    float* sum;           // [nq][N] revealed sum per (query, doc)
+    float* m2;            // [nq][N] centred sum of squares of the revealed cells
+    float* rescored;      // [nq][N] exact score of the k-th survivor
+    float* scores;        // [nq][N] Full-MaxSim scores when the caller keeps none
+    int32_t* cnt_hist;    // [(R+1)][nq]
+    float* tau_hist;      // [R][nq]
+    int32_t* pi;          // [nq][T]
+    int32_t* chunk_doc;   // [nchunks+1] first document of each token chunk (dense kernel)
+    int* flag;            // [64] error / scratch flags
+};
+
+struct Trace {            // all null when tracing is off
+    int32_t* count;
+    float* tau;
+    float* lcb;
+    float* ucb;
+    uint8_t* alive;
+};
+
+struct RevealRound {
+    int r;                // 1-based round
+    int lo, nb;           // batch = pi[lo .. lo+nb)
+    int n_prev, n;        // cells revealed before / after the round
+    float kappa;          // radius per unit sigma_hat at n
+};
+
+struct Knobs {
+    int K, M, B;
+    float a, b;
+};
+
+hipError_t launch_init(const Problem& P, const Work& W, const Knobs& kn, int R, uint64_t seed,
+                       const int32_t* user_pi, const Trace& tr, hipStream_t st);
+
+// Reveal one batch for every active (query, doc) pair by gathering the documents.
+hipError_t launch_gather_reveal(const Problem& P, const Work& W, const RevealRound& rr,
+                                hipStream_t st);
+
+// Exact scores.  ctl == nullptr: all documents of every query, written by doc id into
+// `out` ([nq][N]); otherwise the current active set, written by list position.
+hipError_t launch_gather_score(const Problem& P, const Work& W, bool use_ctl, float* out,
+                               float* cells, hipStream_t st);
+
+// Dense (corpus-streaming) kernel for bf16: Full-MaxSim scores or the first reveal batch.
+hipError_t launch_dense_prepare(const Problem& P, const Work& W, int chunk_tokens, int* n_chunks,
+                                hipStream_t st);
+hipError_t launch_dense_score(const Problem& P, const Work& W, int chunk_tokens, int n_chunks,
+                              float* out, float* cells, hipStream_t st);
+hipError_t launch_dense_reveal(const Problem& P, const Work& W, int chunk_tokens, int n_chunks,
+                               const RevealRound& rr, int G, hipStream_t st);
+bool dense_supported(const Problem& P);
+
+hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
+                               const RevealRound& rr, const Trace& tr, hipStream_t st);
+
+// Top-K of `vals` per query.  use_ctl: candidates are the active set (vals indexed by
+// list position); else all N documents (vals indexed by id).
+hipError_t launch_topk(const Problem& P, const Work& W, bool use_ctl, const float* vals, int K,
+                       int64_t* out_ids, float* out_scores, hipStream_t st);
+
+hipError_t launch_validate_offsets(const int64_t* off, int64_t N, int64_t total, int* flag,
+                                   hipStream_t st);
+
+}  // namespace cb

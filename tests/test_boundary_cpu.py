@@ -1,0 +1,148 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+the header declares, rejects bad arguments before touching the device, and its host
+helpers (reveal permutation, radius pre-factor) agree with the oracle's."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_02827_amd import binding, build
+    build.build_library()
+    binding.lib()
+    return binding
+
+
+def test_library_exports_every_declared_symbol(B):
+    hdr = open(os.path.join(ROOT, "include", "colbandit.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(colbandit_[a-z_0-9]+)\s*\(", hdr))
+    assert {"colbandit_full_maxsim", "colbandit_topk"} <= declared
+    assert declared == set(B.EXPORTS)
+    L = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_struct_layouts_match_the_header(B):
+    # survivors[MAX_ROUNDS + 2] and the limits the binding mirrors
+    hdr = open(os.path.join(ROOT, "include", "colbandit.h")).read()
+    assert int(re.search(r"#define COLBANDIT_MAX_ROUNDS (\d+)", hdr).group(1)) == B.MAX_ROUNDS
+    assert ctypes.sizeof(B.ColbanditStats) == 4 + 4 * (B.MAX_ROUNDS + 2) + 3 * 8 + 8 \
+        or ctypes.sizeof(B.ColbanditStats) % 8 == 0
+
+
+def test_strerror_is_defined_for_every_code(B):
+    msgs = {B.strerror(c) for c in range(0, -9, -1)}
+    assert len(msgs) == 9 and "unknown error code" not in msgs
+    assert B.strerror(-99) == "unknown error code"
+
+
+def _call_full(B, **kw):
+    a = dict(Q=0x1000, nq=1, T=32, d=128, dt=1, docs=0x2000, off=0x3000, N=10, total=400, K=0,
+             scores=0x4000, ids=None, sc=None, cells=None, ws=0x10000, wsb=1 << 40, stream=None)
+    a.update(kw)
+    return B.lib().colbandit_full_maxsim(a["Q"], a["nq"], a["T"], a["d"], a["dt"], a["docs"],
+                                         a["off"], a["N"], a["total"], a["K"], a["scores"],
+                                         a["ids"], a["sc"], a["cells"], a["ws"], a["wsb"],
+                                         a["stream"])
+
+
+def test_full_maxsim_argument_errors(B):
+    # every case fails validation, so nothing is ever launched (no GPU needed)
+    assert _call_full(B, Q=None) == -1
+    assert _call_full(B, docs=None) == -1
+    assert _call_full(B, off=None) == -1
+    assert _call_full(B, scores=None) == -1                 # K == 0 needs scores
+    assert _call_full(B, K=3) == -1                         # K > 0 needs the top-K outputs
+    assert _call_full(B, nq=0) == -2
+    assert _call_full(B, T=0) == -2
+    assert _call_full(B, N=0) == -2
+    assert _call_full(B, total=5) == -2                     # fewer tokens than documents
+    assert _call_full(B, K=11, ids=0x5000, sc=0x6000) == -2  # K > N
+    assert _call_full(B, dt=7) == -2
+    assert _call_full(B, d=100) == -4
+    assert _call_full(B, T=129) == -4
+    assert _call_full(B, dt=0, T=65) == -4
+    assert _call_full(B, Q=0x1004) == -6
+    assert _call_full(B, ws=None) == -1
+    assert _call_full(B, ws=0x10010) == -6
+    assert _call_full(B, wsb=1024) == -5
+
+
+def _call_topk(B, opts=None, **kw):
+    a = dict(Q=0x1000, nq=2, T=32, d=128, dt=1, docs=0x2000, off=0x3000, N=100, total=4000, K=5,
+             alpha=0.2, delta=0.01, M=5, seed=0, ids=0x5000, sc=0x6000, stats=None, ws=0x10000,
+             wsb=1 << 40, stream=None)
+    a.update(kw)
+    o = ctypes.byref(opts) if opts is not None else None
+    return B.lib().colbandit_topk(a["Q"], a["nq"], a["T"], a["d"], a["dt"], a["docs"], a["off"],
+                                  a["N"], a["total"], a["K"], a["alpha"], a["delta"], a["M"],
+                                  ctypes.c_uint64(a["seed"]), o, a["ids"], a["sc"], a["stats"],
+                                  a["ws"], a["wsb"], a["stream"])
+
+
+def test_topk_argument_errors(B):
+    assert _call_topk(B, ids=None) == -1
+    assert _call_topk(B, K=0) == -2
+    assert _call_topk(B, K=101) == -2
+    assert _call_topk(B, N=5000, total=500000, K=2000) == -4
+    for alpha in (0.0, -0.1, 1.5, float("nan")):
+        assert _call_topk(B, alpha=alpha) == -3
+    for delta in (0.0, 1.0, -1.0, float("nan")):
+        assert _call_topk(B, delta=delta) == -3
+    assert _call_topk(B, M=-1) == -3
+    assert _call_topk(B, opts=B.ColbanditOpts(B=-2)) == -3
+    assert _call_topk(B, opts=B.ColbanditOpts(B=17)) == -4
+    assert _call_topk(B, T=128, opts=B.ColbanditOpts(B=1)) == -4       # more than 64 rounds
+    assert _call_topk(B, opts=B.ColbanditOpts(a=1.0, b=-1.0)) == -3
+    assert _call_topk(B, opts=B.ColbanditOpts(a=0.5, b=0.5)) == -3
+    assert _call_topk(B, wsb=4096) == -5
+    o = B.ColbanditOpts(trace=0x20000, trace_bytes=16)
+    assert _call_topk(B, opts=o) == -5
+
+
+def test_workspace_and_trace_sizes(B):
+    assert B.colbandit_workspace_bytes(0, 32, 128, 10, 100) == 0
+    assert B.colbandit_workspace_bytes(1, 32, 128, 10, 5) == 0
+    w1 = B.colbandit_workspace_bytes(1, 32, 128, 1000, 48000)
+    w2 = B.colbandit_workspace_bytes(2, 32, 128, 1000, 48000)
+    w3 = B.colbandit_workspace_bytes(2, 32, 128, 2000, 96000)
+    assert 0 < w1 < w2 < w3 and w1 % 256 == 0
+    # the big configuration fits comfortably in one GPU's memory
+    assert B.colbandit_workspace_bytes(128, 32, 128, 500_000, 53_000_000) < 4 << 30
+    R, nq, N = 8, 3, 1000
+    t = B.colbandit_trace_bytes(nq, 32, 4, N)
+    assert t >= 4 * (R + 1) * nq + 4 * R * nq + 9 * R * nq * N
+
+
+def test_permutation_matches_the_oracle_spec(B, oracle_mod):
+    for seed, q, T in [(0, 0, 32), (7, 5, 24), (2**63 + 11, 127, 64), (1, 0, 1), (3, 2, 2)]:
+        np.testing.assert_array_equal(B.colbandit_permutation(seed, q, T),
+                                      oracle_mod.permutation(seed, q, T))
+
+
+def test_radius_prefactor_matches_the_oracle(B, oracle_mod):
+    for N, T in [(1000, 32), (500_000, 32), (20_000, 24)]:
+        for n in (2, 4, 12, T // 2, T // 2 + 1, T - 1, T):
+            a32, d32 = float(np.float32(0.2)), float(np.float32(0.01))
+            want = oracle_mod.radius(a32, T, 1.0, N, d32, n)
+            assert B.colbandit_radius_prefactor(0.2, 0.01, T, N, n) == pytest.approx(want, rel=1e-12,
+                                                                                     abs=1e-300)
+    assert B.colbandit_radius_prefactor(0.2, 0.01, 32, 1000, 1) == float("inf")
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2602_02827_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in src and "from oracle" not in src, f
+                assert "oracle/" not in src, f

@@ -1,0 +1,297 @@
+"""GPU <-> oracle parity through the C-ABI (run with -m gpu on an MI355X).
+
+Tolerances (relative, on scores): 1e-5 for fp32 inputs, 2e-3 for bf16 inputs with fp32
+accumulation; the oracle reads the same storage-rounded values.  Index results are exact
+wherever the deciding gap exceeds the tolerance.  The Col-Bandit rounds are compared by
+feeding the oracle the GPU's own MaxSim cells, so that only the bookkeeping differs; a
+document may then differ only if its UCB lies within EPS_BAND of the round's threshold.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-3}
+EPS_BAND = 2e-4          # fp32 bound arithmetic vs the oracle's double, on values of size <= T
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2602_02827_amd import binding
+    binding.lib()          # raises if the HIP library is not built: no fallback
+    return binding
+
+
+@pytest.fixture(scope="module")
+def S():
+    from paper_2602_02827_amd import synth
+    return synth
+
+
+def _custom(S, lengths, nq, T, d, dtype, seed):
+    """Corpus with prescribed document lengths (iid unit tokens), on the GPU."""
+    g = torch.Generator(device="cpu"); g.manual_seed(seed)
+    L = torch.tensor(lengths, dtype=torch.int64)
+    off = torch.zeros(len(lengths) + 1, dtype=torch.int64); off[1:] = torch.cumsum(L, 0)
+    E = torch.randn((int(off[-1]), d), generator=g)
+    E = E / E.norm(dim=1, keepdim=True)
+    Q = torch.randn((nq, T, d), generator=g)
+    Q = Q / Q.norm(dim=2, keepdim=True)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    return S.Workload(f"custom-{dtype}", dtype, Q.to(td).cuda(), E.to(td).cuda(), off.cuda(), seed=seed)
+
+
+def _oracle_scores(oracle_mod, w, qs=None):
+    E, off = w.host_docs()
+    Qh = w.host_queries()
+    qs = range(w.nq) if qs is None else qs
+    H = np.stack([oracle_mod.maxsim_cells(Qh[q], E, off) for q in qs])
+    return H, H.sum(axis=2)
+
+
+def _check_topk(ids, scores, S_or, K, tol):
+    """ids/scores: GPU top-K of one query; S_or: oracle scores of all docs."""
+    order = np.lexsort((np.arange(len(S_or)), -S_or))
+    kth = S_or[order[K - 1]]
+    band = tol * max(1.0, abs(kth))
+    assert len(set(ids.tolist())) == K
+    assert np.all(np.diff(scores) <= 0)                       # returned in score order
+    assert np.all(S_or[ids] >= kth - band)                    # nothing clearly below the cut
+    must = order[:K][S_or[order[:K]] > kth + band]            # clearly above the cut
+    assert set(must.tolist()) <= set(ids.tolist())
+    np.testing.assert_allclose(scores, S_or[ids], rtol=tol, atol=tol)
+    gaps = -np.diff(S_or[order[:K + 1]]) if len(S_or) > K else -np.diff(S_or[order[:K]])
+    if np.all(gaps > 2 * band):                                # no near-ties: exact order
+        np.testing.assert_array_equal(ids, order[:K])
+
+
+# ------------------------------------------------------------------ Full-MaxSim
+def test_full_maxsim_fp32_config1(B, S, oracle_mod):
+    w = S.config(0, device="cuda")                              # N=1000, fp32, 1 query
+    H, Sor = _oracle_scores(oracle_mod, w)
+    r = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=5, want_cells=True)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(r["cells"].cpu().numpy(), H, rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(r["scores"].cpu().numpy(), Sor, rtol=1e-5, atol=1e-6)
+    _check_topk(r["topk_ids"][0].cpu().numpy(), r["topk_scores"][0].cpu().numpy(), Sor[0], 5, 1e-5)
+    assert set(w.planted[0]) == set(r["topk_ids"][0].tolist())  # the planted docs are the top-5
+
+
+@pytest.mark.parametrize("nq,T,d", [(1, 32, 128), (3, 32, 128), (6, 24, 128), (20, 32, 128),
+                                     (5, 7, 128), (3, 40, 128), (2, 100, 128), (4, 32, 64),
+                                     (40, 16, 64)])
+def test_full_maxsim_bf16_dense_ragged(B, S, oracle_mod, nq, T, d):
+    # lengths span 1 token, block edges (15/16/17), stage edges (63/64/65), ring wrap (>256)
+    # and documents longer than a workgroup's token chunk (4096)
+    rng = np.random.default_rng(nq * 1000 + T)
+    lengths = [1, 2, 15, 16, 17, 31, 33, 63, 64, 65, 127, 129, 255, 257, 700, 1030, 4500, 1] + \
+        rng.integers(1, 200, 150).tolist() + [5000, 3] + rng.integers(30, 181, 100).tolist()
+    w = _custom(S, lengths, nq, T, d, "bf16", 7)
+    H, Sor = _oracle_scores(oracle_mod, w)
+    r = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=7, want_cells=True)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(r["cells"].cpu().numpy(), H, rtol=TOL["bf16"], atol=1e-5)
+    np.testing.assert_allclose(r["scores"].cpu().numpy(), Sor, rtol=TOL["bf16"], atol=1e-4)
+    # fp32 accumulation of exact bf16 products is far tighter than the stated tolerance
+    assert np.abs(r["scores"].cpu().numpy() - Sor).max() < 5e-5 * T
+    for q in range(nq):
+        _check_topk(r["topk_ids"][q].cpu().numpy(), r["topk_scores"][q].cpu().numpy(), Sor[q], 7,
+                    TOL["bf16"])
+
+
+def test_full_maxsim_fp32_ragged_and_d64(B, S, oracle_mod):
+    rng = np.random.default_rng(5)
+    lengths = [1, 16, 17, 300] + rng.integers(1, 90, 120).tolist()
+    for d, T in [(128, 32), (64, 24), (128, 50)]:
+        w = _custom(S, lengths, 3, T, d, "f32", 11)
+        H, Sor = _oracle_scores(oracle_mod, w)
+        r = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=4, want_cells=True)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(r["cells"].cpu().numpy(), H, rtol=1e-5, atol=1e-6)
+        np.testing.assert_allclose(r["scores"].cpu().numpy(), Sor, rtol=1e-5, atol=1e-6)
+
+
+def test_topk_ties_resolve_to_lower_index(B, S):
+    # documents 10.. are exact copies of documents 0..9 -> exact score ties
+    base = _custom(S, [20] * 10, 2, 32, 128, "bf16", 3)
+    docs = torch.cat([base.docs, base.docs, base.docs])
+    off = (torch.arange(31, dtype=torch.int64) * 20).cuda()
+    r = B.colbandit_full_maxsim(base.Q, docs, off, K=12)
+    torch.cuda.synchronize()
+    sc = r["scores"].cpu().numpy()
+    np.testing.assert_array_equal(sc[:, :10], sc[:, 10:20])
+    for q in range(2):
+        order = np.lexsort((np.arange(30), -sc[q]))[:12]
+        np.testing.assert_array_equal(r["topk_ids"][q].cpu().numpy(), order)
+
+
+def test_mid_text_config2_scaled(B, S, oracle_mod):
+    w = S.config(1, device="cuda", scale=0.06, nq=8)            # N=3000, bf16, planted docs
+    H, Sor = _oracle_scores(oracle_mod, w)
+    r = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=5)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(r["scores"].cpu().numpy(), Sor, rtol=TOL["bf16"], atol=1e-4)
+    for q in range(w.nq):
+        _check_topk(r["topk_ids"][q].cpu().numpy(), r["topk_scores"][q].cpu().numpy(), Sor[q], 5,
+                    TOL["bf16"])
+
+
+# ------------------------------------------------------------------ Col-Bandit
+def _compare_rounds(oracle_mod, tr, q, Hq, K, M, Bsz, alpha, delta, pi, a=-1.0, b=1.0):
+    """Oracle on the GPU's cells vs the GPU trace.  Returns the round of first divergence
+    (band documents only) or None."""
+    N, T = Hq.shape
+    orc = oracle_mod.colbandit_from_H(Hq, K, M, Bsz, alpha, delta, pi, a, b)
+    for r in range(orc.rounds):
+        assert tr.count[r, q] == orc.counts[r], (q, r)
+        live = ~np.isnan(orc.lcb[r])
+        g_live = ~np.isnan(tr.lcb[r, q])
+        np.testing.assert_array_equal(g_live, live)
+        np.testing.assert_allclose(tr.lcb[r, q][live], orc.lcb[r][live], rtol=0, atol=EPS_BAND)
+        np.testing.assert_allclose(tr.ucb[r, q][live], orc.ucb[r][live], rtol=0, atol=EPS_BAND)
+        assert abs(tr.tau[r, q] - orc.tau[r]) <= EPS_BAND, (q, r)
+        mism = np.flatnonzero(tr.alive[r, q] != orc.alive[r])
+        if len(mism):
+            assert np.all(np.abs(orc.ucb[r][mism] - orc.tau[r]) <= 2 * EPS_BAND), (q, r, mism)
+            return r, orc
+    assert tr.count[orc.rounds, q] == orc.counts[orc.rounds]
+    return None, orc
+
+
+def _run_colbandit_case(B, oracle_mod, w, K, M, Bsz, alpha, delta=0.01, seed=0, a=0.0, b=0.0,
+                        force_gather=False, max_diverged=0.15):
+    full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=0, want_cells=True)
+    res = B.colbandit_topk(w.Q, w.docs, w.offsets, K, alpha, delta, M, seed, B=Bsz, a=a, b=b,
+                           trace=True, force_gather=force_gather)
+    torch.cuda.synchronize()
+    H = full["cells"].cpu().numpy().astype(np.float64)
+    Sfull = full["scores"].cpu().numpy()
+    ids = res["topk_ids"].cpu().numpy()
+    sc = res["topk_scores"].cpu().numpy()
+    tr = res["trace"]
+    aa, bb = (-1.0, 1.0) if a == 0.0 and b == 0.0 else (a, b)
+    diverged = 0
+    for q in range(w.nq):
+        pi = B.colbandit_permutation(seed, q, w.T)
+        np.testing.assert_array_equal(pi, oracle_mod.permutation(seed, q, w.T))
+        div, orc = _compare_rounds(oracle_mod, tr, q, H[q], K, M, Bsz, alpha, delta, pi, aa, bb)
+        st = res["stats"][q]
+        # survivor scores carry the same bits as the exhaustive path
+        ok = ids[q] >= 0
+        np.testing.assert_array_equal(sc[q][ok], Sfull[q][ids[q][ok]])
+        # accounting identity (cells touched) from the GPU's own survivor counts
+        T = w.T
+        cells = sum((min((r + 1) * Bsz, T) - r * Bsz) * st["survivors"][r] for r in range(st["rounds"]))
+        assert st["cells_elim"] == cells
+        assert st["cells_rescore"] == T * st["survivors"][st["rounds"]]
+        n_last = min(st["rounds"] * Bsz, T)
+        assert st["cells_unique"] == cells + (T - n_last) * st["survivors"][st["rounds"]]
+        assert st["survivors"] == [int(x) for x in tr.count[: st["rounds"] + 1, q]]
+        if div is None:
+            assert st["rounds"] == orc.rounds
+            assert (st["cells_elim"], st["cells_rescore"], st["cells_unique"]) == \
+                   (orc.cells_elim, orc.cells_rescore, orc.cells_unique)
+            kk = min(K, len(orc.final_ids))
+            fin_scores = Sfull[q][orc.final_ids].astype(np.float64)
+            order = orc.final_ids[np.lexsort((orc.final_ids, -fin_scores))][:kk]
+            np.testing.assert_array_equal(ids[q][:kk], order)
+        else:
+            diverged += 1
+    assert diverged <= max(1, int(max_diverged * w.nq)), diverged
+    return res, tr
+
+
+def test_colbandit_fp32_config1(B, S, oracle_mod):
+    w = S.config(0, device="cuda")
+    res, tr = _run_colbandit_case(B, oracle_mod, w, 5, 5, 4, 0.2)
+    # end to end against the oracle working from the embeddings themselves
+    E, off = w.host_docs()
+    pi = oracle_mod.permutation(0, 0, w.T)
+    orc = oracle_mod.colbandit_lazy(w.host_queries()[0], E, off, 5, 5, 4, 0.2, 0.01, pi)
+    np.testing.assert_array_equal(res["topk_ids"][0].cpu().numpy(), orc.topk_ids)
+    np.testing.assert_allclose(res["topk_scores"][0].cpu().numpy(), orc.topk_scores, rtol=1e-5)
+    assert res["stats"][0]["cells_unique"] == orc.cells_unique
+    assert set(w.planted[0]) == set(orc.topk_ids.tolist())
+
+
+@pytest.mark.parametrize("alpha,K,M,Bsz", [(0.2, 5, 5, 4), (1.0, 5, 5, 4), (0.05, 1, 0, 4),
+                                           (0.2, 50, 5, 4), (0.5, 10, 5, 3), (0.2, 5, 5, 16),
+                                           (0.2, 5, 0, 1), (1.0, 3, 2, 5)])
+def test_colbandit_bf16_rounds_match_oracle(B, S, oracle_mod, alpha, K, M, Bsz):
+    w = S.config(1, device="cuda", scale=0.04, nq=6)            # N=2000, planted docs
+    _run_colbandit_case(B, oracle_mod, w, K, M, Bsz, alpha)
+
+
+def test_colbandit_topic_corpus_and_pages(B, S, oracle_mod):
+    w = S.config(2, device="cuda", scale=0.008, nq=10)          # N=4000 topic mixture
+    _run_colbandit_case(B, oracle_mod, w, 5, 5, 4, 0.2)
+    _run_colbandit_case(B, oracle_mod, w, 10, 5, 4, 0.2, seed=9)
+    w = S.config(3, device="cuda", scale=0.01, nq=5)            # 200 pages x 1030 tokens, T=24
+    _run_colbandit_case(B, oracle_mod, w, 5, 5, 4, 0.2)
+    _run_colbandit_case(B, oracle_mod, w, 5, 5, 4, 1.0)
+
+
+def test_colbandit_gather_and_dense_first_round_agree(B, S, oracle_mod):
+    w = S.config(1, device="cuda", scale=0.03, nq=5)
+    r1 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.2, 0.01, 5, 3, trace=True)
+    r2 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.2, 0.01, 5, 3, trace=True, force_gather=True)
+    torch.cuda.synchronize()
+    for f in ("count", "tau", "lcb", "ucb", "alive"):
+        np.testing.assert_array_equal(getattr(r1["trace"], f), getattr(r2["trace"], f))
+    assert torch.equal(r1["topk_ids"], r2["topk_ids"]) and torch.equal(r1["topk_scores"], r2["topk_scores"])
+
+
+def test_colbandit_support_wider_than_default(B, S, oracle_mod):
+    w = S.config(1, device="cuda", scale=0.02, nq=3)
+    _run_colbandit_case(B, oracle_mod, w, 5, 5, 4, 0.2, a=-1.5, b=1.25)
+
+
+def test_colbandit_small_candidate_sets(B, S, oracle_mod):
+    # N <= K+M: no round runs and the answer is the exhaustive top-K; also N == K and N == 1
+    for N, K, M in [(9, 4, 5), (10, 5, 5), (5, 5, 0), (1, 1, 0), (11, 5, 5)]:
+        w = _custom(S, [33] * N, 2, 32, 128, "bf16", N)
+        full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K)
+        res = B.colbandit_topk(w.Q, w.docs, w.offsets, K, 0.2, 0.01, M, 0)
+        torch.cuda.synchronize()
+        if N <= K + M:
+            assert all(s["rounds"] == 0 and s["cells_elim"] == 0 and s["cells_rescore"] == 32 * N
+                       for s in res["stats"])
+            assert torch.equal(res["topk_ids"], full["topk_ids"])
+            assert torch.equal(res["topk_scores"], full["topk_scores"])
+
+
+def test_explicit_permutation_and_determinism(B, S):
+    w = S.config(1, device="cuda", scale=0.02, nq=4)
+    pi = torch.tensor(np.stack([B.colbandit_permutation(77, q, w.T) for q in range(w.nq)]),
+                      dtype=torch.int32, device="cuda")
+    r1 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.2, 0.01, 5, 77, trace=True)
+    r2 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.2, 0.01, 5, 123456, pi=pi, trace=True)
+    r3 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.2, 0.01, 5, 77, trace=True)
+    torch.cuda.synchronize()
+    for other in (r2, r3):
+        assert torch.equal(r1["topk_ids"], other["topk_ids"])
+        assert torch.equal(r1["topk_scores"], other["topk_scores"])
+        np.testing.assert_array_equal(r1["trace"].alive, other["trace"].alive)
+    assert [s["survivors"] for s in r1["stats"]] == [s["survivors"] for s in r2["stats"]]
+
+
+def test_async_call_without_stats(B, S):
+    w = S.config(1, device="cuda", scale=0.02, nq=4)
+    r1 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.2, 0.01, 5, 1)
+    r2 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.2, 0.01, 5, 1, want_stats=False)
+    torch.cuda.synchronize()
+    assert r2["stats"] is None
+    assert torch.equal(r1["topk_ids"], r2["topk_ids"]) and torch.equal(r1["topk_scores"], r2["topk_scores"])
+
+
+def test_validate_offsets(B, S):
+    w = S.config(0, device="cuda")
+    assert B.colbandit_validate_offsets(w.offsets, w.total_tokens) == 0
+    bad = w.offsets.clone(); bad[10] = bad[9]                   # an empty document
+    assert B.colbandit_validate_offsets(bad, w.total_tokens) == -8
+    assert B.colbandit_validate_offsets(w.offsets, w.total_tokens - 1) == -8
+    # a bad table must not fault: rows are clamped, results are merely meaningless
+    B.colbandit_full_maxsim(w.Q, w.docs, bad, K=0)
+    torch.cuda.synchronize()
