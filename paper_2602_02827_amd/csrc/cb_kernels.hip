@@ -36,7 +36,10 @@ __global__ void k_init(QueryCtl* ctl, int32_t* pi, const int32_t* user_pi, int32
     }
     int32_t* p = pi + (size_t)q * T;
     if (user_pi) {
-        for (int t = 0; t < T; ++t) p[t] = user_pi[(size_t)q * T + t];
+        for (int t = 0; t < T; ++t) {   // clamped: a bad table must not steer a read out of Q
+            const int32_t v = user_pi[(size_t)q * T + t];
+            p[t] = v < 0 ? 0 : (v >= T ? T - 1 : v);
+        }
     } else {
         // Fisher-Yates driven by SplitMix64 (Sec. 4.2: one seeded uniform permutation per query)
         uint64_t s = seed + ((uint64_t)q + 1ull) * 0x9E3779B97F4A7C15ull;
