@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcolbandit.so")
 SOURCES = ["cb_api.hip", "cb_kernels.hip", "cb_dense.hip"]
 HEADERS = ["cb_device.h", "cb_launch.h", os.path.join("..", "..", "include", "colbandit.h")]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-Xarch_device", "-fno-honor-nans", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms are kept off for the device code of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -17,7 +17,7 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 constexpr int kChunkTokens = 4096;
 
 struct Layout {
-    size_t ctl, list0, list1, sum, m2, rescored, scores, cnt_hist, tau_hist, pi, chunk_doc, flag,
+    size_t ctl, list0, list1, stat, rescored, scores, cnt_hist, tau_hist, pi, chunk_doc, flag,
         total;
 };
 
@@ -33,8 +33,7 @@ Layout make_layout(int nq, int T, int64_t N, int64_t total_tokens) {
     L.ctl = take(sizeof(QueryCtl) * (size_t)nq);
     L.list0 = take(4 * qn);
     L.list1 = take(4 * qn);
-    L.sum = take(4 * qn);
-    L.m2 = take(4 * qn);
+    L.stat = take(8 * qn);
     L.rescored = take(4 * qn);
     L.scores = take(4 * qn);
     L.cnt_hist = take(4 * (size_t)(COLBANDIT_MAX_ROUNDS + 2) * nq);
@@ -52,8 +51,7 @@ Work carve(void* ws, const Layout& L) {
     W.ctl = (QueryCtl*)(b + L.ctl);
     W.list[0] = (int32_t*)(b + L.list0);
     W.list[1] = (int32_t*)(b + L.list1);
-    W.sum = (float*)(b + L.sum);
-    W.m2 = (float*)(b + L.m2);
+    W.stat = (float2*)(b + L.stat);
     W.rescored = (float*)(b + L.rescored);
     W.scores = (float*)(b + L.scores);
     W.cnt_hist = (int32_t*)(b + L.cnt_hist);

@@ -42,8 +42,7 @@ struct DenseArgs {
     // reveal
     const int32_t* pi;
     int lo, nb, G;
-    float* sum;
-    float* m2;
+    float2* stat;
 };
 
 template <int D, int NT, int TQ, bool REVEAL>
@@ -143,44 +142,65 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt) h[tt] = -__builtin_inff();
 
+    // per-document epilogue: cross-lane maxima, then the row sum (score) or the batch
+    // statistics (reveal), written by the lanes that own a query
     auto finalize = [&](int doc) {
-        if (REVEAL) {
+        if constexpr (REVEAL) {
+            using P = Pack<NT>;
+            float w[P::NW];
+            P::colmax(h, w);
+            const int row = lane >> 4;
 #pragma unroll
-            for (int tt = 0; tt < NT; ++tt) {
-                const float hv = colmax_rows(h[tt]);
-                const int x = (tile0 + tt) * 16 + col;
+            for (int j = 0; j < P::NW; ++j) {
+                const int x = (tile0 + P::tile_of_row(j, row)) * 16 + col;
                 const int q = x / A.G, sl = x % A.G;
                 float sb, m2b;
-                batch_stats(hv, sl, A.nb, A.G, sb, m2b);
-                if (lane < 16 && sl == 0 && q < A.nq) {
-                    const size_t p = (size_t)q * A.N + doc;
-                    A.sum[p] = sb;
-                    A.m2[p] = m2b;
-                }
+                batch_stats(w[j], sl, A.nb, A.G, sb, m2b);
+                if (sl == 0 && q < A.nq && P::row_is_primary(row))
+                    A.stat[(size_t)q * A.N + doc] = make_float2(sb, m2b);
             }
         } else {
+            using SC = Score<NT, TQ>;
+            float w[SC::NW], sc[SC::NS];
+            SC::run(h, A.T, col, w, sc);
 #pragma unroll
-            for (int j = 0; j < NT / TQ; ++j) {
-                float hq[TQ];
+            for (int j = 0; j < SC::NS; ++j) {
+                const int lq = SC::writer(j, lane);
+                const int q = tile0 / TQ + lq;
+                if (lq >= 0 && q < A.nq) A.out[(size_t)q * A.N + doc] = sc[j];
+            }
+            if (A.cells) {
+                const int row = lane >> 4;
 #pragma unroll
-                for (int tt = 0; tt < TQ; ++tt) hq[tt] = colmax_rows(h[j * TQ + tt]);
-                const float s = score_from_colmax<TQ>(hq, A.T, col);
-                const int q = (tile0 + j * TQ) / TQ;
-                if (q < A.nq) {
-                    if (lane == 0) A.out[(size_t)q * A.N + doc] = s;
-                    if (A.cells && lane < 16) {
-#pragma unroll
-                        for (int tt = 0; tt < TQ; ++tt) {
-                            const int t = tt * 16 + col;
-                            if (t < A.T) A.cells[((size_t)q * A.N + doc) * A.T + t] = hq[tt];
-                        }
-                    }
+                for (int j = 0; j < SC::NW; ++j) {
+                    const int g = tile0 + Pack<NT>::tile_of_row(j, row);
+                    const int q = g / TQ, t = (g % TQ) * 16 + col;
+                    if (Pack<NT>::row_is_primary(row) && q < A.nq && t < A.T)
+                        A.cells[((size_t)q * A.N + doc) * A.T + t] = w[j];
                 }
             }
         }
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) h[tt] = -__builtin_inff();
     };
+
+    // one block of 16 tokens against all NT column tiles
+    auto compute = [&](const F& a) {
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) {
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+            F::mma(acc, a, bq[tt]);
+            h[tt] = fold_max(h[tt], acc);
+        }
+    };
+    // A fragment of the block whose lane row sits at ring byte offset `ro`; `co` are the
+    // lane's swizzled piece offsets
+    auto load_a = [&](F& a, int ro, const int (&co)[F::KS]) {
+#pragma unroll
+        for (int ks = 0; ks < F::KS; ++ks) a.v[ks] = *(const bf16x8_t*)(ring + ro + co[ks]);
+    };
+    constexpr int RING_BYTES = RING_ROWS * ROWB;
+    constexpr int BLOCK_BYTES = 16 * ROWB;
 
     const int nst = (ntok + STAGE_ROWS - 1) / STAGE_ROWS;
     stage_fetch(0);
@@ -191,7 +211,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
     }
     __syncthreads();
 
-    int doc = i0 - 1;      // current document; its tokens are [dbeg, dend) relative to tok_begin
+    int doc = i0 - 1;      // current document; its tokens are [.., dend) relative to tok_begin
     int dend = 0, cur = 0;
     bool started = false, finished = false;
 
@@ -213,23 +233,44 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
                 dend = rel_off(doc + 1);
                 continue;
             }
-            const int last = (cur + 16 < dend ? cur + 16 : dend) - 1;
-            if (last >= avail) break;
-            int row = cur + col;
-            row = row < dend ? row : dend - 1;
-            const char* rp = ring + (row & (RING_ROWS - 1)) * ROWB;
-            const int sw = row & (NCH - 1);
-            F a;
+            // blocks of this document that are complete in the ring: n full ones, and the
+            // short last one if the document ends inside what has arrived
+            const int lim = dend < avail ? dend : avail;
+            int n = (lim - cur) >> 4;
+            const bool tail = dend <= avail && ((dend - cur) & 15) != 0;
+            if (n == 0 && !tail) break;
+            const int row0 = cur + col;
+            const int sw = row0 & (NCH - 1);          // blocks step by 16 rows: sw is invariant
+            int co[F::KS];
 #pragma unroll
-            for (int ks = 0; ks < F::KS; ++ks)
-                a.v[ks] = *(const bf16x8_t*)(rp + (((ks * 4 + kg) ^ sw) * 16));
-#pragma unroll
-            for (int tt = 0; tt < NT; ++tt) {
-                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-                F::mma(acc, a, bq[tt]);
-                h[tt] = fmaxf(h[tt], max4(acc));
+            for (int ks = 0; ks < F::KS; ++ks) co[ks] = ((ks * 4 + kg) ^ sw) * 16;
+            int ro = (row0 & (RING_ROWS - 1)) * ROWB;
+            cur += n * 16;
+            if (n > 0) {
+                F a0, a1;
+                load_a(a0, ro, co);
+                while (n >= 2) {                       // two blocks per trip, loads one ahead
+                    load_a(a1, (ro + BLOCK_BYTES) & (RING_BYTES - 1), co);
+                    compute(a0);
+                    ro = (ro + 2 * BLOCK_BYTES) & (RING_BYTES - 1);
+                    if (n > 2) load_a(a0, ro, co);
+                    compute(a1);
+                    n -= 2;
+                }
+                if (n == 1) compute(a0);
             }
-            cur += 16;
+            if (tail) {                                // rows past the end repeat the last token
+                int row = cur + col;
+                row = row < dend ? row : dend - 1;
+                const int swt = row & (NCH - 1);
+                const int rot = (row & (RING_ROWS - 1)) * ROWB;
+                F a;
+#pragma unroll
+                for (int ks = 0; ks < F::KS; ++ks)
+                    a.v[ks] = *(const bf16x8_t*)(ring + rot + (((ks * 4 + kg) ^ swt) * 16));
+                compute(a);
+                cur = dend;
+            }
         }
         if (more) stage_commit(s + 2);
         __syncthreads();
@@ -274,8 +315,7 @@ static void fill_dense(DenseArgs& A, const Problem& P, const Work& W, int n_chun
     A.T = P.T;
     A.n_chunks = n_chunks;
     A.pi = W.pi;
-    A.sum = W.sum;
-    A.m2 = W.m2;
+    A.stat = W.stat;
 }
 
 template <int D, int NT, int TQ, bool REVEAL>

@@ -77,51 +77,182 @@ template <int D> struct Frag<f32_tag, D> {
 __device__ __forceinline__ float max4(const f32x4_t& c) {
     return fmaxf(fmaxf(c[0], c[1]), fmaxf(c[2], c[3]));
 }
+// running maximum h <- max(h, c0..c3), two three-input maxima
+__device__ __forceinline__ float fold_max(float h, const f32x4_t& c) {
+    const float t = fmaxf(fmaxf(c[0], c[1]), c[2]);
+    return fmaxf(fmaxf(h, t), c[3]);
+}
 
-// Max over the four row groups of a column: afterwards every lane of a column holds
-// the column's maximum over all 16 rows.
-__device__ __forceinline__ float colmax_rows(float v) {
-    v = fmaxf(v, __shfl_xor(v, 16));
-    v = fmaxf(v, __shfl_xor(v, 32));
+// ---------------------------------------------------------------------------------
+// Cross-lane helpers.  A wavefront is four rows of 16 lanes; row = lane >> 4 is the
+// accumulator's row group, col = lane & 15 its column.  DPP moves data inside a row,
+// v_permlane32_swap / v_permlane16_swap exchange rows between two registers:
+//   swap32(a,b): a' = [a.r0 a.r1 b.r0 b.r1]   b' = [a.r2 a.r3 b.r2 b.r3]
+//   swap16(a,b): a' = [a.r0 b.r0 a.r2 b.r2]   b' = [a.r1 b.r1 a.r3 b.r3]
+// ---------------------------------------------------------------------------------
+constexpr int DPP_QUAD_XOR1 = 0xB1;    // quad_perm [1,0,3,2]
+constexpr int DPP_QUAD_XOR2 = 0x4E;    // quad_perm [2,3,0,1]
+constexpr int DPP_ROW_MIRROR = 0x140;
+constexpr int DPP_ROW_HALF_MIRROR = 0x141;
+constexpr int DPP_ROW_ROR = 0x120;     // + n: lane c reads lane (c - n) mod 16 of its row
+
+template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ void swap32(float& a, float& b) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    const unsigned r0 = r[0], r1 = r[1];   // copy the elements out before reinterpreting them
+    a = __uint_as_float(r0);
+    b = __uint_as_float(r1);
+}
+__device__ __forceinline__ void swap16(float& a, float& b) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    const unsigned r0 = r[0], r1 = r[1];   // copy the elements out before reinterpreting them
+    a = __uint_as_float(r0);
+    b = __uint_as_float(r1);
+}
+// rows 0,1 <- max over (r0,r2),(r1,r3) of a; rows 2,3 <- the same of b
+__device__ __forceinline__ float maxpack32(float a, float b) {
+    swap32(a, b);
+    return fmaxf(a, b);
+}
+// rows 0,2 <- max over (r0,r1),(r2,r3) of a; rows 1,3 <- the same of b
+__device__ __forceinline__ float maxpack16(float a, float b) {
+    swap16(a, b);
+    return fmaxf(a, b);
+}
+// every lane <- w[lane] + w[lane ^ 32] (lower-row operand first in every lane)
+__device__ __forceinline__ float addswap32(float w) {
+    float a = w, b = w;
+    swap32(a, b);
+    return a + b;
+}
+// every lane <- w[lane] + w[lane ^ 16] (even-row operand first in every lane)
+__device__ __forceinline__ float addswap16(float w) {
+    float a = w, b = w;
+    swap16(a, b);
+    return a + b;
+}
+// Sum of the 16 columns of a row by four rotations.  The association order depends on
+// the lane, so only column 0's value is the canonical one (it is the only one stored).
+__device__ __forceinline__ float rowsum16(float v) {
+    v += dpp_mov<DPP_ROW_ROR + 8>(v);
+    v += dpp_mov<DPP_ROW_ROR + 4>(v);
+    v += dpp_mov<DPP_ROW_ROR + 2>(v);
+    v += dpp_mov<DPP_ROW_ROR + 1>(v);
+    return v;
+}
+// Sum over aligned groups of G consecutive columns, G in {1,2,4,8,16}; slot 0 of the group
+// holds the canonical value.
+template <int G> __device__ __forceinline__ float sum_group(float v) {
+    if (G >= 16) v += dpp_mov<DPP_ROW_MIRROR>(v);
+    if (G >= 8) v += dpp_mov<DPP_ROW_HALF_MIRROR>(v);
+    if (G >= 4) v += dpp_mov<DPP_QUAD_XOR2>(v);
+    if (G >= 2) v += dpp_mov<DPP_QUAD_XOR1>(v);
     return v;
 }
 
-// Sum over the 16 columns (lanes sharing lane >> 4); fixed butterfly order.
-__device__ __forceinline__ float sum_cols16(float v) {
-    v += __shfl_xor(v, 8);
-    v += __shfl_xor(v, 4);
-    v += __shfl_xor(v, 2);
-    v += __shfl_xor(v, 1);
-    return v;
-}
-
-// Sum over aligned groups of G consecutive columns (G a power of two <= 16).
-__device__ __forceinline__ float sum_group(float v, int G) {
-    for (int o = G >> 1; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-
-// Late-interaction score from the per-column maxima of one query (TQ column tiles,
-// column c of tile tt is query token 16*tt + c): tokens >= T contribute 0, tiles are
-// added in ascending order, then the 16 columns by butterfly.  Every kernel that
-// produces a score goes through here, so equal cells give equal bits.
-template <int TQ>
-__device__ __forceinline__ float score_from_colmax(const float (&h)[TQ], int T, int col) {
-    float s = 0.f;
+// Packing of NT per-tile running maxima (each lane: its column, its row group's 4 rows)
+// into registers whose ROWS are tiles: after pack_colmax every lane of row r of w[j]
+// holds the maximum over all 16 accumulator rows of column col of tile tile_of_row(j, r).
+template <int NT> struct Pack {
+    static constexpr int NW = NT >= 4 ? NT / 4 : 1;
+    // which tile sits in row `row` of packed register j
+    __device__ __forceinline__ static int tile_of_row(int j, int row) {
+        if (NT >= 4) return 4 * j + (((row & 1) << 1) | (row >> 1));
+        if (NT == 2) return row >> 1;
+        return 0;
+    }
+    // rows that hold a tile not already held by a lower row
+    __device__ __forceinline__ static bool row_is_primary(int row) {
+        if (NT >= 4) return true;
+        if (NT == 2) return (row & 1) == 0;
+        return row == 0;
+    }
+    __device__ __forceinline__ static void colmax(const float (&h)[NT], float (&w)[NW]) {
+        if constexpr (NT == 1) {
+            const float m = maxpack32(h[0], h[0]);
+            w[0] = maxpack16(m, m);
+        } else if constexpr (NT == 2) {
+            const float m = maxpack32(h[0], h[1]);
+            w[0] = maxpack16(m, m);
+        } else {
 #pragma unroll
-    for (int tt = 0; tt < TQ; ++tt) s += (tt * 16 + col < T) ? h[tt] : 0.f;
-    return sum_cols16(s);
-}
+            for (int j = 0; j < NW; ++j) {
+                const float m0 = maxpack32(h[4 * j], h[4 * j + 1]);
+                const float m1 = maxpack32(h[4 * j + 2], h[4 * j + 3]);
+                w[j] = maxpack16(m0, m1);
+            }
+        }
+    }
+};
 
-// Statistics of one reveal batch held in a group of G columns (slot = col % G, the
-// first nb slots are real): sum and centred sum of squares of the nb cells.
-__device__ __forceinline__ void batch_stats(float h, int slot, int nb, int G, float& s,
-                                            float& m2) {
+// Late-interaction scores from NT tile maxima, TQ consecutive tiles per query (column c of
+// a query's tile k is query token 16k + c; tokens >= T count as 0).  Fixed order: tiles are
+// added pairwise (t0+t1), then ((t0+t1)+(t2+t3)), then the two halves of 8, then the 16
+// columns by rowsum16.  Every kernel that produces a score goes through here, so equal
+// cells give equal bits.  Outputs: w = packed cells (masked), s[j] = score register j.
+// Use score_writer() to find the lanes that own a query's score.
+template <int NT, int TQ> struct Score {
+    using P = Pack<NT>;
+    static constexpr int NW = P::NW;
+    static constexpr int NS = TQ == 8 ? 1 : NW;
+    __device__ __forceinline__ static void run(float (&h)[NT], int T, int col, float (&w)[NW],
+                                               float (&s)[NS]) {
+        if (T != TQ * 16) {
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt)
+                if ((tt % TQ) * 16 + col >= T) h[tt] = 0.f;
+        }
+        P::colmax(h, w);
+        if constexpr (TQ == 1) {
+#pragma unroll
+            for (int j = 0; j < NW; ++j) s[j] = rowsum16(w[j]);
+        } else if constexpr (TQ == 2) {
+#pragma unroll
+            for (int j = 0; j < NW; ++j) s[j] = rowsum16(addswap32(w[j]));
+        } else if constexpr (TQ == 4) {
+#pragma unroll
+            for (int j = 0; j < NW; ++j) s[j] = rowsum16(addswap16(addswap32(w[j])));
+        } else {
+            const float y0 = addswap16(addswap32(w[0]));
+            const float y1 = addswap16(addswap32(w[1]));
+            s[0] = rowsum16(y0 + y1);
+        }
+    }
+    // local query index (0 .. NT/TQ-1) whose score lane `lane` holds in s[j], or -1
+    __device__ __forceinline__ static int writer(int j, int lane) {
+        const int row = lane >> 4;
+        if ((lane & 15) != 0) return -1;
+        if (TQ == 1) return P::row_is_primary(row) ? P::tile_of_row(j, row) : -1;
+        if (TQ == 2) {
+            if (NT >= 4) return row < 2 ? 2 * j + row : -1;
+            return row == 0 ? 0 : -1;
+        }
+        return row == 0 ? j : -1;
+    }
+};
+
+// Statistics of one reveal batch held in a group of G columns (slot = column % G, the
+// first nb slots are real): sum and centred sum of squares of the nb cells; canonical at
+// slot 0.
+template <int G>
+__device__ __forceinline__ void batch_stats_g(float h, int slot, int nb, float& s, float& m2) {
     const bool valid = slot < nb;
-    s = sum_group(valid ? h : 0.f, G);
+    s = sum_group<G>(valid ? h : 0.f);
     const float mean = s / (float)nb;
     const float dv = valid ? (h - mean) : 0.f;
-    m2 = sum_group(dv * dv, G);
+    m2 = sum_group<G>(dv * dv);
+}
+__device__ __forceinline__ void batch_stats(float h, int slot, int nb, int G, float& s, float& m2) {
+    switch (G) {
+        case 1: batch_stats_g<1>(h, slot, nb, s, m2); break;
+        case 2: batch_stats_g<2>(h, slot, nb, s, m2); break;
+        case 4: batch_stats_g<4>(h, slot, nb, s, m2); break;
+        case 8: batch_stats_g<8>(h, slot, nb, s, m2); break;
+        default: batch_stats_g<16>(h, slot, nb, s, m2); break;
+    }
 }
 
 // Merge a batch (nb cells: sum sb, centred squares m2b) into a document's running

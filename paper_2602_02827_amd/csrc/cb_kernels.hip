@@ -100,9 +100,8 @@ struct GatherArgs {
     const int32_t* list1;
     // reveal
     const int32_t* pi;
-    int lo, nb, n_prev;
-    float* sum;
-    float* m2;
+    int lo, nb, n_prev, G;
+    float2* stat;
     // score
     float* out;
     float* cells;
@@ -164,34 +163,32 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
             for (int tt = 0; tt < TQ; ++tt) {
                 f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
                 F::mma(acc, a, bq[tt]);
-                h[tt] = fmaxf(h[tt], max4(acc));
+                h[tt] = fold_max(h[tt], acc);
             }
         }
-#pragma unroll
-        for (int tt = 0; tt < TQ; ++tt) h[tt] = colmax_rows(h[tt]);
-
-        if (REVEAL) {
-            float sb, m2b;
-            batch_stats(h[0], col, A.nb, 16, sb, m2b);
+        if constexpr (REVEAL) {
+            float w[1], sb, m2b;
+            Pack<1>::colmax(h, w);
+            batch_stats(w[0], col % A.G, A.nb, A.G, sb, m2b);
             if (lane == 0) {
                 const size_t x = (size_t)q * A.N + id;
-                float S = 0.f, M2 = 0.f;
-                if (A.n_prev > 0) {
-                    S = A.sum[x];
-                    M2 = A.m2[x];
-                }
-                merge_stats(S, M2, A.n_prev, sb, m2b, A.nb);
-                A.sum[x] = S;
-                A.m2[x] = M2;
+                float2 st = make_float2(0.f, 0.f);
+                if (A.n_prev > 0) st = A.stat[x];
+                merge_stats(st.x, st.y, A.n_prev, sb, m2b, A.nb);
+                A.stat[x] = st;
             }
         } else {
-            const float s = score_from_colmax<TQ>(h, A.T, col);
-            if (lane == 0) A.out[(size_t)q * A.N + (A.ctl ? k : id)] = s;
-            if (A.cells && lane < 16) {
+            using SC = Score<TQ, TQ>;
+            float w[SC::NW], sc[SC::NS];
+            SC::run(h, A.T, col, w, sc);
+            if (lane == 0) A.out[(size_t)q * A.N + (A.ctl ? k : id)] = sc[0];
+            if (A.cells) {
+                const int row = lane >> 4;
 #pragma unroll
-                for (int tt = 0; tt < TQ; ++tt) {
-                    const int t = tt * 16 + col;
-                    if (t < A.T) A.cells[((size_t)q * A.N + id) * A.T + t] = h[tt];
+                for (int j = 0; j < SC::NW; ++j) {
+                    const int t = Pack<TQ>::tile_of_row(j, row) * 16 + col;
+                    if (Pack<TQ>::row_is_primary(row) && t < A.T)
+                        A.cells[((size_t)q * A.N + id) * A.T + t] = w[j];
                 }
             }
         }
@@ -228,8 +225,7 @@ static void fill_gather_common(GatherArgs& A, const Problem& P, const Work& W) {
     A.list0 = W.list[0];
     A.list1 = W.list[1];
     A.pi = W.pi;
-    A.sum = W.sum;
-    A.m2 = W.m2;
+    A.stat = W.stat;
 }
 
 template <typename Tag>
@@ -247,6 +243,8 @@ hipError_t launch_gather_reveal(const Problem& P, const Work& W, const RevealRou
     A.lo = rr.lo;
     A.nb = rr.nb;
     A.n_prev = rr.n_prev;
+    A.G = 1;
+    while (A.G < rr.nb) A.G <<= 1;
     return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, true, P, st)
                            : gather_by_d<f32_tag>(A, true, P, st);
 }
@@ -357,8 +355,7 @@ struct SelArgs {
     QueryCtl* ctl;
     int32_t* list0;
     int32_t* list1;
-    const float* sum;
-    const float* m2;
+    const float2* stat;
     int64_t N;
     int nq, T, K, KM;
     int r, n;
@@ -389,15 +386,15 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
     const int32_t* in = c.implicit ? nullptr : (c.cur ? A.list1 : A.list0) + (size_t)q * A.N;
     const int out_sel = c.implicit ? 0 : (c.cur ^ 1);
     int32_t* out = (out_sel ? A.list1 : A.list0) + (size_t)q * A.N;
-    const float* sum = A.sum + (size_t)q * A.N;
-    const float* m2 = A.m2 + (size_t)q * A.N;
+    const float2* stat = A.stat + (size_t)q * A.N;
     const int n = A.n, T = A.T;
     const float kappa = A.kappa, a = A.a, b = A.b;
 
     auto key_of = [&](int idx) -> uint32_t {
         const int id = in ? in[idx] : idx;
         float lcb, ucb;
-        interval(sum[id], m2[id], n, T, kappa, a, b, lcb, ucb);
+        const float2 st = stat[id];
+        interval(st.x, st.y, n, T, kappa, a, b, lcb, ucb);
         return float_key(lcb);
     };
     const uint32_t tkey = block_kth_largest(count, A.K, key_of, hist, pick);
@@ -412,7 +409,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
         if (idx < count) {
             id = in ? in[idx] : idx;
             float lcb, ucb;
-            interval(sum[id], m2[id], n, T, kappa, a, b, lcb, ucb);
+            const float2 st = stat[id];
+            interval(st.x, st.y, n, T, kappa, a, b, lcb, ucb);
             keep = ucb >= tau;
             if (A.tr_lcb) {
                 A.tr_lcb[tro + id] = lcb;
@@ -447,8 +445,7 @@ hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
     A.ctl = W.ctl;
     A.list0 = W.list[0];
     A.list1 = W.list[1];
-    A.sum = W.sum;
-    A.m2 = W.m2;
+    A.stat = W.stat;
     A.N = P.N;
     A.nq = P.nq;
     A.T = P.T;

@@ -21,8 +21,7 @@ struct Problem {
 struct Work {
     QueryCtl* ctl;        // [nq]
     int32_t* list[2];     // [nq][N] each: ids of the active set, ascending
-    float* sum;           // [nq][N] revealed sum per (query, doc)
-    float* m2;            // [nq][N] centred sum of squares of the revealed cells
+    float2* stat;         // [nq][N] per (query, doc): revealed sum, centred sum of squares
     float* rescored;      // [nq][N] exact score of the k-th survivor
     float* scores;        // [nq][N] Full-MaxSim scores when the caller keeps none
     int32_t* cnt_hist;    // [(R+1)][nq]
