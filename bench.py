@@ -107,6 +107,9 @@ def main():
     coverage = cells_unique / cells_total
     rounds = [s["rounds"] for s in st]
     surv1 = float(np.mean([s["survivors"][1] if s["rounds"] >= 1 else N for s in st]))
+    max_r = max(rounds)
+    surv_by_round = [round(float(np.mean([s["survivors"][min(r, s["rounds"])] for s in st])), 1)
+                     for r in range(max_r + 1)]
     same_bits = bool(all(
         torch.equal(res["topk_scores"][q], out_full["scores"][q][res["topk_ids"][q]]) for q in range(nq)))
 
@@ -136,6 +139,7 @@ def main():
                       "coverage": round(coverage, 4), "overlap_at_k": round(overlap, 4),
                       "mean_rounds": round(float(np.mean(rounds)), 2),
                       "mean_survivors_after_round1": round(surv1, 1),
+                      "mean_survivors_by_round": surv_by_round,
                       "speedup_vs_full": round(ms_full / ms_cb, 2),
                       "survivor_scores_bit_identical_to_full": same_bits},
         "roofline": roofline,
