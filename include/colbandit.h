@@ -78,6 +78,9 @@ typedef struct {
     size_t trace_bytes;
     int force_gather;   /* nonzero: reveal round 1 with the gather kernel as well
                            (test aid; the default picks the dense kernel for bf16)      */
+    int no_cell_cache;  /* nonzero: re-gather the documents in every round instead of
+                           caching a small active set's cells at its first gather
+                           (test aid; the decisions are the same either way)            */
 } colbandit_opts;
 
 /*

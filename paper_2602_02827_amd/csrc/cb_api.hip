@@ -18,8 +18,12 @@ constexpr int kChunkTokens = 4096;
 
 struct Layout {
     size_t ctl, list0, list1, stat, rescored, scores, cnt_hist, tau_hist, pi, chunk_doc, flag,
-        total;
+        cid, cstat, ccell, total;
+    int cache_cap, TP;
 };
+
+// Slots per query in the cell cache.
+constexpr int64_t kCacheCapMax = 16384;
 
 Layout make_layout(int nq, int T, int64_t N, int64_t total_tokens) {
     Layout L{};
@@ -41,6 +45,14 @@ Layout make_layout(int nq, int T, int64_t N, int64_t total_tokens) {
     L.pi = take(4 * (size_t)nq * T);
     L.chunk_doc = take(4 * (size_t)(total_tokens / kChunkTokens + 16));
     L.flag = take(256);
+    L.cache_cap = (int)(N < kCacheCapMax ? N : kCacheCapMax);
+    {   // floats per cached document: whole 16-column tiles, in the kernels' 1/2/4/8 tile shapes
+        const int tq = (T + 15) / 16;
+        L.TP = 16 * (tq <= 1 ? 1 : tq <= 2 ? 2 : tq <= 4 ? 4 : 8);
+    }
+    L.cid = take(4 * (size_t)nq * L.cache_cap);
+    L.cstat = take(8 * (size_t)nq * L.cache_cap);
+    L.ccell = take(4 * (size_t)nq * L.cache_cap * L.TP);
     L.total = o;
     return L;
 }
@@ -59,6 +71,11 @@ Work carve(void* ws, const Layout& L) {
     W.pi = (int32_t*)(b + L.pi);
     W.chunk_doc = (int32_t*)(b + L.chunk_doc);
     W.flag = (int*)(b + L.flag);
+    W.cache_cap = L.cache_cap;
+    W.TP = L.TP;
+    W.cid = (int32_t*)(b + L.cid);
+    W.cstat = (float2*)(b + L.cstat);
+    W.ccell = (float*)(b + L.ccell);
     return W;
 }
 
@@ -212,7 +229,7 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
     const int32_t* user_pi = nullptr;
     void* trace = nullptr;
     size_t trace_bytes = 0;
-    bool force_gather = false;
+    bool force_gather = false, no_cache = false;
     if (opts) {
         if (opts->B < 0) return COLBANDIT_ERR_KNOB;
         if (opts->B > 0) kn.B = opts->B;
@@ -225,6 +242,7 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
         trace = opts->trace;
         trace_bytes = opts->trace_bytes;
         force_gather = opts->force_gather != 0;
+        no_cache = opts->no_cell_cache != 0;
     }
     if (kn.B > COLBANDIT_MAX_B) return COLBANDIT_ERR_UNSUPPORTED;
     const int R = (T + kn.B - 1) / kn.B;
@@ -250,7 +268,8 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
         tr.alive = (uint8_t*)b;
     }
 
-    const Work W = carve(workspace, L);
+    Work W = carve(workspace, L);
+    if (no_cache) W.cache_cap = 0;
     const Problem P{Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens};
     hipStream_t st = (hipStream_t)stream;
 
@@ -281,10 +300,12 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
             e = launch_dense_reveal(P, W, kChunkTokens, n_chunks, rr, G, st);
         } else {
             e = launch_gather_reveal(P, W, rr, st);
+            if (e == hipSuccess && r >= 2) e = launch_gather_cells(P, W, rr, st);
         }
         if (e == hipSuccess) e = launch_select_prune(P, W, kn, rr, tr, st);
     }
     if (e == hipSuccess) e = launch_gather_score(P, W, true, W.rescored, nullptr, st);
+    if (e == hipSuccess) e = launch_cached_score(P, W, W.rescored, st);
     if (e == hipSuccess) e = launch_topk(P, W, true, W.rescored, K, topk_ids, topk_scores, st);
     if (e != hipSuccess) {
         if (stats) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); }

@@ -5,6 +5,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// No fused multiply-add contraction anywhere in this library's device code: the same
+// formula must give the same bits in every kernel it is inlined into (the bound updates run
+// in a cross-lane form and in a one-thread form).
+#pragma clang fp contract(off)
+
 namespace cb {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -22,6 +27,8 @@ struct QueryCtl {
     int cur;       // which of the two id lists holds A
     int implicit;  // 1: A = [0,N) and no list exists
     int active;    // 1: the query still takes part in elimination rounds
+    int mode;      // 0: list entries are document ids; 1: they are slots of the cell cache
+    int pad0, pad1, pad2;
 };
 
 // ---------------------------------------------------------------------------------
@@ -162,6 +169,13 @@ template <int NT> struct Pack {
     __device__ __forceinline__ static int tile_of_row(int j, int row) {
         if (NT >= 4) return 4 * j + (((row & 1) << 1) | (row >> 1));
         if (NT == 2) return row >> 1;
+        return 0;
+    }
+    // a row that holds tile `tile` of its packed register (tile taken modulo 4)
+    __device__ __forceinline__ static int row_of_tile(int tile) {
+        const int k = tile & 3;
+        if (NT >= 4) return ((k & 1) << 1) | (k >> 1);
+        if (NT == 2) return (k & 1) << 1;
         return 0;
     }
     // rows that hold a tile not already held by a lower row

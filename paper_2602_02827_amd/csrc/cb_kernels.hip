@@ -25,14 +25,16 @@ __global__ void k_init(QueryCtl* ctl, int32_t* pi, const int32_t* user_pi, int32
     c.cur = 0;
     c.implicit = 1;
     c.active = N > (int64_t)KM;
+    c.mode = 0;
+    c.pad0 = c.pad1 = c.pad2 = 0;
     ctl[q] = c;
     for (int r = 0; r <= R; ++r) {
         cnt_hist[r * nq + q] = (int)N;
         if (tr_count) tr_count[r * nq + q] = (int)N;
     }
     for (int r = 0; r < R; ++r) {
-        tau_hist[r * nq + q] = __builtin_nanf("");
-        if (tr_tau) tr_tau[r * nq + q] = __builtin_nanf("");
+        tau_hist[r * nq + q] = __uint_as_float(0x7fc00000u);   // quiet NaN: "round not run"
+        if (tr_tau) tr_tau[r * nq + q] = __uint_as_float(0x7fc00000u);
     }
     int32_t* p = pi + (size_t)q * T;
     if (user_pi) {
@@ -85,10 +87,22 @@ hipError_t launch_init(const Problem& P, const Work& W, const Knobs& kn, int R, 
 // document's tokens from global memory in blocks of 16 rows (A operand, rows past the
 // end of the document repeat its last token, which cannot change a max), runs the MFMA
 // chain over d and folds the 16x16 result into a running per-column maximum.
-//   REVEAL: one 16-column tile, column c < nb is query token pi[lo+c]; the epilogue
-//           merges the batch into the pair's (sum, M2).       [Algorithm 1, reveal step]
-//   score : TQ tiles = all T tokens; the epilogue is the row sum. [Eq. (2); rescore step]
+//   GM_REVEAL: one 16-column tile, column c < nb is query token pi[lo+c]; the epilogue
+//              merges the batch into the pair's (sum, M2).     [Algorithm 1, reveal step]
+//   GM_SCORE : TQ tiles = all T tokens; the epilogue is the row sum. [Eq. (2); rescore]
+//   GM_CELLS : TQ tiles = all T tokens; the epilogue stores the pair's T cells in the
+//              query's cell cache, merges this round's batch from them and turns the
+//              list entry into a cache slot.  A gathered reveal is bound by the bytes of
+//              the document, not by the cells computed from them, so a document is
+//              visited once and the later rounds (and the rescore) read its cells back;
+//              the order in which cells are REVEALED to the bounds is unchanged.
+// Which queries a launch serves (uniform per query, from QueryCtl):
+//   GM_REVEAL: active, ids mode, and (implicit or count > cache_cap)
+//   GM_CELLS : active, ids mode, not implicit, count <= cache_cap
+//   GM_SCORE : ctl == nullptr (all documents) or ids mode
 // =====================================================================================
+enum { GM_REVEAL = 0, GM_SCORE = 1, GM_CELLS = 2 };
+
 struct GatherArgs {
     const void* Q;
     const void* docs;
@@ -96,18 +110,23 @@ struct GatherArgs {
     int64_t N, total;
     int T;
     const QueryCtl* ctl;      // nullptr: every query scores all N documents
-    const int32_t* list0;
-    const int32_t* list1;
+    int32_t* list0;
+    int32_t* list1;
     // reveal
     const int32_t* pi;
     int lo, nb, n_prev, G;
     float2* stat;
+    // cell cache
+    int cache_cap, TP;
+    int32_t* cid;
+    float2* cstat;
+    float* ccell;
     // score
     float* out;
     float* cells;
 };
 
-template <typename Tag, int D, int TQ, bool REVEAL>
+template <typename Tag, int D, int TQ, int MODE>
 __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
     using F = Frag<Tag, D>;
     const int q = blockIdx.y;
@@ -118,10 +137,14 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
     const size_t row_bytes = (size_t)D * F::ELEM_BYTES;
 
     int count = (int)A.N;
-    const int32_t* list = nullptr;
+    int32_t* list = nullptr;
     if (A.ctl) {
         const QueryCtl c = A.ctl[q];
-        if (REVEAL && !c.active) return;
+        if (c.mode != 0) return;
+        if (MODE != GM_SCORE && !c.active) return;
+        const bool cacheable = !c.implicit && c.count <= A.cache_cap;
+        if (MODE == GM_REVEAL && cacheable) return;
+        if (MODE == GM_CELLS && !cacheable) return;
         count = c.count;
         if (!c.implicit) list = (c.cur ? A.list1 : A.list0) + (size_t)q * A.N;
     }
@@ -134,7 +157,7 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
 #pragma unroll
     for (int tt = 0; tt < TQ; ++tt) {
         int trow;
-        if (REVEAL) {
+        if (MODE == GM_REVEAL) {
             trow = A.pi[(size_t)q * A.T + A.lo + (col < A.nb ? col : 0)];
         } else {
             const int t = tt * 16 + col;
@@ -166,7 +189,8 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
                 h[tt] = fold_max(h[tt], acc);
             }
         }
-        if constexpr (REVEAL) {
+
+        if constexpr (MODE == GM_REVEAL) {
             float w[1], sb, m2b;
             Pack<1>::colmax(h, w);
             batch_stats(w[0], col % A.G, A.nb, A.G, sb, m2b);
@@ -176,6 +200,35 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
                 if (A.n_prev > 0) st = A.stat[x];
                 merge_stats(st.x, st.y, A.n_prev, sb, m2b, A.nb);
                 A.stat[x] = st;
+            }
+        } else if constexpr (MODE == GM_CELLS) {
+            using P = Pack<TQ>;
+            float w[P::NW];
+            P::colmax(h, w);
+            const int row = lane >> 4;
+            const size_t slot = (size_t)q * A.cache_cap + k;
+            float* crow = A.ccell + slot * A.TP;
+#pragma unroll
+            for (int j = 0; j < P::NW; ++j)
+                if (P::row_is_primary(row)) crow[P::tile_of_row(j, row) * 16 + col] = w[j];
+            // this round's batch: slot s (lane s of row 0) fetches cell pi[lo+s] from its owner
+            const int sl = lane < A.nb ? lane : 0;
+            const int t = A.pi[(size_t)q * A.T + A.lo + sl];
+            const int tile = t >> 4;
+            const int src = P::row_of_tile(tile) * 16 + (t & 15);
+            float v = __shfl(w[0], src);
+            if constexpr (P::NW > 1) {
+                const float v1 = __shfl(w[1], src);
+                v = tile >= 4 ? v1 : v;
+            }
+            float sb, m2b;
+            batch_stats(v, col % A.G, A.nb, A.G, sb, m2b);
+            if (lane == 0) {
+                float2 st = A.stat[(size_t)q * A.N + id];
+                merge_stats(st.x, st.y, A.n_prev, sb, m2b, A.nb);
+                A.cstat[slot] = st;
+                A.cid[slot] = id;
+                list[k] = k;          // the entry now names its cache slot
             }
         } else {
             using SC = Score<TQ, TQ>;
@@ -195,24 +248,31 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
     }
 }
 
+template <typename Tag, int D, int MODE>
+static hipError_t gather_tq(const GatherArgs& A, dim3 grid, hipStream_t st) {
+    const dim3 block(256);
+    const int tq = (A.T + 15) / 16;
+    if (tq <= 1) k_gather<Tag, D, 1, MODE><<<grid, block, 0, st>>>(A);
+    else if (tq <= 2) k_gather<Tag, D, 2, MODE><<<grid, block, 0, st>>>(A);
+    else if (tq <= 4) k_gather<Tag, D, 4, MODE><<<grid, block, 0, st>>>(A);
+    else if constexpr (Tag::wide) k_gather<Tag, D, 8, MODE><<<grid, block, 0, st>>>(A);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 template <typename Tag, int D>
-static hipError_t gather_dispatch(const GatherArgs& A, bool reveal, int nq, int64_t max_count,
+static hipError_t gather_dispatch(const GatherArgs& A, int mode, int nq, int64_t max_count,
                                   hipStream_t st) {
     int gx = (int)((max_count + 3) / 4);
     if (gx > 256) gx = 256;
     if (gx < 1) gx = 1;
-    const dim3 grid(gx, nq), block(256);
-    if (reveal) {
-        k_gather<Tag, D, 1, true><<<grid, block, 0, st>>>(A);
-    } else {
-        const int tq = (A.T + 15) / 16;
-        if (tq <= 1) k_gather<Tag, D, 1, false><<<grid, block, 0, st>>>(A);
-        else if (tq <= 2) k_gather<Tag, D, 2, false><<<grid, block, 0, st>>>(A);
-        else if (tq <= 4) k_gather<Tag, D, 4, false><<<grid, block, 0, st>>>(A);
-        else if constexpr (Tag::wide) k_gather<Tag, D, 8, false><<<grid, block, 0, st>>>(A);
-        else return hipErrorInvalidValue;
+    const dim3 grid(gx, nq);
+    if (mode == GM_REVEAL) {
+        k_gather<Tag, D, 1, GM_REVEAL><<<grid, dim3(256), 0, st>>>(A);
+        return hipGetLastError();
     }
-    return hipGetLastError();
+    if (mode == GM_CELLS) return gather_tq<Tag, D, GM_CELLS>(A, grid, st);
+    return gather_tq<Tag, D, GM_SCORE>(A, grid, st);
 }
 
 static void fill_gather_common(GatherArgs& A, const Problem& P, const Work& W) {
@@ -226,13 +286,27 @@ static void fill_gather_common(GatherArgs& A, const Problem& P, const Work& W) {
     A.list1 = W.list[1];
     A.pi = W.pi;
     A.stat = W.stat;
+    A.cache_cap = W.cache_cap;
+    A.TP = W.TP;
+    A.cid = W.cid;
+    A.cstat = W.cstat;
+    A.ccell = W.ccell;
 }
 
 template <typename Tag>
-static hipError_t gather_by_d(const GatherArgs& A, bool reveal, const Problem& P, hipStream_t st) {
-    if (P.d == 128) return gather_dispatch<Tag, 128>(A, reveal, P.nq, P.N, st);
-    if (P.d == 64) return gather_dispatch<Tag, 64>(A, reveal, P.nq, P.N, st);
+static hipError_t gather_by_d(const GatherArgs& A, int mode, const Problem& P, int64_t max_count,
+                              hipStream_t st) {
+    if (P.d == 128) return gather_dispatch<Tag, 128>(A, mode, P.nq, max_count, st);
+    if (P.d == 64) return gather_dispatch<Tag, 64>(A, mode, P.nq, max_count, st);
     return hipErrorInvalidValue;
+}
+
+static void fill_round(GatherArgs& A, const RevealRound& rr) {
+    A.lo = rr.lo;
+    A.nb = rr.nb;
+    A.n_prev = rr.n_prev;
+    A.G = 1;
+    while (A.G < rr.nb) A.G <<= 1;
 }
 
 hipError_t launch_gather_reveal(const Problem& P, const Work& W, const RevealRound& rr,
@@ -240,13 +314,20 @@ hipError_t launch_gather_reveal(const Problem& P, const Work& W, const RevealRou
     GatherArgs A{};
     fill_gather_common(A, P, W);
     A.ctl = W.ctl;
-    A.lo = rr.lo;
-    A.nb = rr.nb;
-    A.n_prev = rr.n_prev;
-    A.G = 1;
-    while (A.G < rr.nb) A.G <<= 1;
-    return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, true, P, st)
-                           : gather_by_d<f32_tag>(A, true, P, st);
+    fill_round(A, rr);
+    return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, GM_REVEAL, P, P.N, st)
+                           : gather_by_d<f32_tag>(A, GM_REVEAL, P, P.N, st);
+}
+
+hipError_t launch_gather_cells(const Problem& P, const Work& W, const RevealRound& rr,
+                               hipStream_t st) {
+    if (W.cache_cap <= 0) return hipSuccess;
+    GatherArgs A{};
+    fill_gather_common(A, P, W);
+    A.ctl = W.ctl;
+    fill_round(A, rr);
+    return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, GM_CELLS, P, W.cache_cap, st)
+                           : gather_by_d<f32_tag>(A, GM_CELLS, P, W.cache_cap, st);
 }
 
 hipError_t launch_gather_score(const Problem& P, const Work& W, bool use_ctl, float* out,
@@ -256,8 +337,50 @@ hipError_t launch_gather_score(const Problem& P, const Work& W, bool use_ctl, fl
     A.ctl = use_ctl ? W.ctl : nullptr;
     A.out = out;
     A.cells = cells;
-    return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, false, P, st)
-                           : gather_by_d<f32_tag>(A, false, P, st);
+    return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, GM_SCORE, P, P.N, st)
+                           : gather_by_d<f32_tag>(A, GM_SCORE, P, P.N, st);
+}
+
+// Exact scores of cached survivors: the T cells of a slot are laid out as the column
+// maxima of TQ tiles and summed by the same routine as everywhere else (same bits).
+struct CachedScoreArgs {
+    const QueryCtl* ctl;
+    const int32_t* list0;
+    const int32_t* list1;
+    const float* ccell;
+    int64_t N;
+    int T, TP, cache_cap;
+    float* out;
+};
+
+template <int TQ>
+__global__ __launch_bounds__(256) void k_cached_score(CachedScoreArgs A) {
+    const int q = blockIdx.y;
+    const QueryCtl c = A.ctl[q];
+    if (c.mode != 1) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 15;
+    const int32_t* list = (c.cur ? A.list1 : A.list0) + (size_t)q * A.N;
+    using SC = Score<TQ, TQ>;
+    for (int k = blockIdx.x * 4 + wave; k < c.count; k += gridDim.x * 4) {
+        const float* crow = A.ccell + ((size_t)q * A.cache_cap + list[k]) * A.TP;
+        float h[TQ], w[SC::NW], sc[SC::NS];
+#pragma unroll
+        for (int tt = 0; tt < TQ; ++tt) h[tt] = crow[tt * 16 + col];
+        SC::run(h, A.T, col, w, sc);
+        if (lane == 0) A.out[(size_t)q * A.N + k] = sc[0];
+    }
+}
+
+hipError_t launch_cached_score(const Problem& P, const Work& W, float* out, hipStream_t st) {
+    if (W.cache_cap <= 0) return hipSuccess;
+    CachedScoreArgs A{W.ctl, W.list[0], W.list[1], W.ccell, P.N, P.T, W.TP, W.cache_cap, out};
+    const dim3 grid(16, P.nq), block(256);
+    const int tq = (P.T + 15) / 16;
+    if (tq <= 1) k_cached_score<1><<<grid, block, 0, st>>>(A);
+    else if (tq <= 2) k_cached_score<2><<<grid, block, 0, st>>>(A);
+    else if (tq <= 4) k_cached_score<4><<<grid, block, 0, st>>>(A);
+    else k_cached_score<8><<<grid, block, 0, st>>>(A);
+    return hipGetLastError();
 }
 
 // =====================================================================================
@@ -265,6 +388,8 @@ hipError_t launch_gather_score(const Problem& P, const Work& W, bool use_ctl, fl
 // =====================================================================================
 constexpr int SEL_THREADS = 1024;
 constexpr int SEL_WAVES = SEL_THREADS / 64;
+constexpr int SEL_ITEMS = 4;                       // consecutive entries per thread per chunk
+constexpr int SEL_CHUNK = SEL_THREADS * SEL_ITEMS;
 
 // Exclusive scan of v over the block in thread order; returns the thread's offset and the
 // block total.  wtot: LDS int[SEL_WAVES].  Two barriers.
@@ -291,7 +416,8 @@ __device__ __forceinline__ int block_excl_scan(int v, int* wtot, int& total) {
 }
 
 // Key of the K-th largest element (1 <= K <= count) of key_of(0..count-1): three radix
-// passes (11+11+10 bits) over the candidates with an LDS histogram each.
+// passes (11+11+10 bits) over the candidates with an LDS histogram each.  Each thread
+// takes SEL_ITEMS strided entries per trip so that several loads are in flight.
 // hist: LDS uint32[2048]; pick: LDS int[2].
 template <class KeyFn>
 __device__ uint32_t block_kth_largest(int count, int K, KeyFn key_of, uint32_t* hist, int* pick) {
@@ -307,9 +433,19 @@ __device__ uint32_t block_kth_largest(int count, int K, KeyFn key_of, uint32_t* 
             pick[1] = 1;
         }
         __syncthreads();
-        for (int idx = threadIdx.x; idx < count; idx += SEL_THREADS) {
-            const uint32_t key = key_of(idx);
-            if ((key & pmask) == prefix) atomicAdd(&hist[(key >> shift) & (nbins - 1)], 1u);
+        for (int base = 0; base < count; base += SEL_CHUNK) {
+            uint32_t key[SEL_ITEMS];
+#pragma unroll
+            for (int u = 0; u < SEL_ITEMS; ++u) {
+                const int idx = base + u * SEL_THREADS + threadIdx.x;
+                key[u] = idx < count ? key_of(idx) : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < SEL_ITEMS; ++u) {
+                const int idx = base + u * SEL_THREADS + threadIdx.x;
+                if (idx < count && (key[u] & pmask) == prefix)
+                    atomicAdd(&hist[(key[u] >> shift) & (nbins - 1)], 1u);
+            }
         }
         __syncthreads();
         if (threadIdx.x < 64) {
@@ -347,9 +483,47 @@ __device__ uint32_t block_kth_largest(int count, int K, KeyFn key_of, uint32_t* 
     return prefix;
 }
 
+// The batch statistics of batch_stats_g<G> evaluated by ONE thread on the G slot values
+// (same pairing of additions, lane by lane, so the bits are those of the cross-lane form).
+__device__ __forceinline__ void lanes_sum(float (&v)[16], int G) {
+    float t[16];
+    if (G >= 16) {
+        for (int i = 0; i < 16; ++i) t[i] = v[i] + v[15 - i];
+        for (int i = 0; i < 16; ++i) v[i] = t[i];
+    }
+    if (G >= 8) {
+        for (int i = 0; i < 16; ++i) t[i] = v[i] + v[(i & 8) | (7 - (i & 7))];
+        for (int i = 0; i < 16; ++i) v[i] = t[i];
+    }
+    if (G >= 4) {
+        for (int i = 0; i < 16; ++i) t[i] = v[i] + v[i ^ 2];
+        for (int i = 0; i < 16; ++i) v[i] = t[i];
+    }
+    if (G >= 2) {
+        for (int i = 0; i < 16; ++i) t[i] = v[i] + v[i ^ 1];
+        for (int i = 0; i < 16; ++i) v[i] = t[i];
+    }
+}
+__device__ __forceinline__ void batch_stats_thread(const float (&c)[16], int nb, int G, float& s,
+                                                   float& m2) {
+    float v[16];
+    for (int i = 0; i < 16; ++i) v[i] = (i < nb) ? c[i] : 0.f;
+    lanes_sum(v, G);
+    s = v[0];
+    float dv[16];
+    for (int i = 0; i < 16; ++i) {
+        const float d = (i < nb) ? (c[i] - v[i] / (float)nb) : 0.f;
+        dv[i] = d * d;
+    }
+    lanes_sum(dv, G);
+    m2 = dv[0];
+}
+
 // =====================================================================================
 // threshold + prune: tau_r = K-th largest LCB over the active set, A_{r+1} = {UCB >= tau_r}
 // (Algorithm 1, threshold and elimination steps), one workgroup per query, stable.
+// For a query whose cells are cached the round's reveal is folded in first: each entry's
+// (sum, M2) takes the batch pi[lo..lo+nb) from its cached cells.
 // =====================================================================================
 struct SelArgs {
     QueryCtl* ctl;
@@ -358,8 +532,13 @@ struct SelArgs {
     const float2* stat;
     int64_t N;
     int nq, T, K, KM;
-    int r, n;
+    int r, n, n_prev, lo, nb, G;
     float kappa, a, b;
+    const int32_t* pi;
+    int cache_cap, TP;
+    const int32_t* cid;
+    float2* cstat;
+    const float* ccell;
     int32_t* cnt_hist;
     float* tau_hist;
     int32_t* tr_count;
@@ -386,14 +565,35 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
     const int32_t* in = c.implicit ? nullptr : (c.cur ? A.list1 : A.list0) + (size_t)q * A.N;
     const int out_sel = c.implicit ? 0 : (c.cur ^ 1);
     int32_t* out = (out_sel ? A.list1 : A.list0) + (size_t)q * A.N;
-    const float2* stat = A.stat + (size_t)q * A.N;
+    // entries are cache slots if the query was switched earlier (mode 1) or by this
+    // round's cell-caching gather (same rule as in k_gather)
+    const bool slots = c.mode == 1 || (c.mode == 0 && !c.implicit && count <= A.cache_cap);
+    const float2* stat = slots ? A.cstat + (size_t)q * A.cache_cap : A.stat + (size_t)q * A.N;
+    const int32_t* cid = A.cid + (size_t)q * A.cache_cap;
     const int n = A.n, T = A.T;
     const float kappa = A.kappa, a = A.a, b = A.b;
 
+    if (c.mode == 1) {          // fold this round's batch in from the cached cells
+        float2* cst = A.cstat + (size_t)q * A.cache_cap;
+        const int32_t* pq = A.pi + (size_t)q * T + A.lo;
+        for (int idx = threadIdx.x; idx < count; idx += SEL_THREADS) {
+            const int e = in[idx];
+            const float* crow = A.ccell + ((size_t)q * A.cache_cap + e) * A.TP;
+            float cv[16];
+            for (int i = 0; i < 16; ++i) cv[i] = i < A.nb ? crow[pq[i]] : 0.f;
+            float sb, m2b;
+            batch_stats_thread(cv, A.nb, A.G, sb, m2b);
+            float2 st = cst[e];
+            merge_stats(st.x, st.y, A.n_prev, sb, m2b, A.nb);
+            cst[e] = st;
+        }
+        __syncthreads();
+    }
+
     auto key_of = [&](int idx) -> uint32_t {
-        const int id = in ? in[idx] : idx;
+        const int e = in ? in[idx] : idx;
         float lcb, ucb;
-        const float2 st = stat[id];
+        const float2 st = stat[e];
         interval(st.x, st.y, n, T, kappa, a, b, lcb, ucb);
         return float_key(lcb);
     };
@@ -402,25 +602,38 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
 
     const size_t tro = ((size_t)(A.r - 1) * A.nq + q) * A.N;
     int base = 0;
-    for (int start = 0; start < count; start += SEL_THREADS) {
-        const int idx = start + threadIdx.x;
-        int id = -1;
-        bool keep = false;
-        if (idx < count) {
-            id = in ? in[idx] : idx;
-            float lcb, ucb;
-            const float2 st = stat[id];
-            interval(st.x, st.y, n, T, kappa, a, b, lcb, ucb);
-            keep = ucb >= tau;
-            if (A.tr_lcb) {
-                A.tr_lcb[tro + id] = lcb;
-                A.tr_ucb[tro + id] = ucb;
-                A.tr_alive[tro + id] = keep ? 1 : 0;
+    for (int start = 0; start < count; start += SEL_CHUNK) {
+        const int i0 = start + threadIdx.x * SEL_ITEMS;     // SEL_ITEMS consecutive entries
+        int e[SEL_ITEMS];
+        float2 st[SEL_ITEMS];
+#pragma unroll
+        for (int u = 0; u < SEL_ITEMS; ++u) {
+            const int idx = i0 + u;
+            e[u] = idx < count ? (in ? in[idx] : idx) : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < SEL_ITEMS; ++u) st[u] = (i0 + u < count) ? stat[e[u]] : make_float2(0.f, 0.f);
+        unsigned keep = 0;
+#pragma unroll
+        for (int u = 0; u < SEL_ITEMS; ++u) {
+            if (i0 + u < count) {
+                float lcb, ucb;
+                interval(st[u].x, st[u].y, n, T, kappa, a, b, lcb, ucb);
+                const bool kp = ucb >= tau;
+                keep |= (kp ? 1u : 0u) << u;
+                if (A.tr_lcb) {
+                    const int id = slots ? cid[e[u]] : e[u];
+                    A.tr_lcb[tro + id] = lcb;
+                    A.tr_ucb[tro + id] = ucb;
+                    A.tr_alive[tro + id] = kp ? 1 : 0;
+                }
             }
         }
         int total;
-        const int pos = block_excl_scan(keep ? 1 : 0, wtot, total);
-        if (keep) out[base + pos] = id;
+        int pos = base + block_excl_scan(__popc(keep), wtot, total);
+#pragma unroll
+        for (int u = 0; u < SEL_ITEMS; ++u)
+            if (keep & (1u << u)) out[pos++] = e[u];
         base += total;
     }
     if (threadIdx.x == 0) {
@@ -429,6 +642,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
         nc.cur = out_sel;
         nc.implicit = 0;
         nc.active = base > A.KM;
+        nc.mode = slots ? 1 : 0;
+        nc.pad0 = nc.pad1 = nc.pad2 = 0;
         A.ctl[q] = nc;
         A.cnt_hist[A.r * A.nq + q] = base;
         A.tau_hist[(A.r - 1) * A.nq + q] = tau;
@@ -453,9 +668,20 @@ hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
     A.KM = kn.K + kn.M;
     A.r = rr.r;
     A.n = rr.n;
+    A.n_prev = rr.n_prev;
+    A.lo = rr.lo;
+    A.nb = rr.nb;
+    A.G = 1;
+    while (A.G < rr.nb) A.G <<= 1;
     A.kappa = rr.kappa;
     A.a = kn.a;
     A.b = kn.b;
+    A.pi = W.pi;
+    A.cache_cap = W.cache_cap;
+    A.TP = W.TP;
+    A.cid = W.cid;
+    A.cstat = W.cstat;
+    A.ccell = W.ccell;
     A.cnt_hist = W.cnt_hist;
     A.tau_hist = W.tau_hist;
     A.tr_count = tr.count;
@@ -476,6 +702,8 @@ struct TopkArgs {
     const QueryCtl* ctl;   // nullptr: all N documents, vals indexed by id
     const int32_t* list0;
     const int32_t* list1;
+    const int32_t* cid;
+    int cache_cap;
     const float* vals;     // [nq][N]
     int64_t N;
     int K;
@@ -492,10 +720,12 @@ __global__ __launch_bounds__(SEL_THREADS) void k_topk(TopkArgs A) {
     const int q = blockIdx.x;
     int count = (int)A.N;
     const int32_t* list = nullptr;
+    const int32_t* cid = nullptr;
     if (A.ctl) {
         const QueryCtl c = A.ctl[q];
         count = c.count;
         if (!c.implicit) list = (c.cur ? A.list1 : A.list0) + (size_t)q * A.N;
+        if (c.mode == 1) cid = A.cid + (size_t)q * A.cache_cap;
     }
     const float* vals = A.vals + (size_t)q * A.N;
     const int Kq = A.K < count ? A.K : count;
@@ -504,34 +734,52 @@ __global__ __launch_bounds__(SEL_THREADS) void k_topk(TopkArgs A) {
         const uint32_t tkey = block_kth_largest(count, Kq, key_of, hist, pick);
         // how many are strictly above the K-th value
         int gt_local = 0;
-        for (int idx = threadIdx.x; idx < count; idx += SEL_THREADS)
-            gt_local += float_key(vals[idx]) > tkey;
+        for (int base = 0; base < count; base += SEL_CHUNK) {
+#pragma unroll
+            for (int u = 0; u < SEL_ITEMS; ++u) {
+                const int idx = base + u * SEL_THREADS + threadIdx.x;
+                if (idx < count) gt_local += float_key(vals[idx]) > tkey;
+            }
+        }
         int n_gt;
         block_excl_scan(gt_local, wtot, n_gt);
         const int need_eq = Kq - n_gt;
         int base_gt = 0, base_eq = 0;
-        for (int start = 0; start < count; start += SEL_THREADS) {
-            const int idx = start + threadIdx.x;
-            bool gt = false, eq = false;
-            float v = 0.f;
-            if (idx < count) {
-                v = vals[idx];
-                const uint32_t key = float_key(v);
-                gt = key > tkey;
-                eq = key == tkey;
+        for (int start = 0; start < count; start += SEL_CHUNK) {
+            const int i0 = start + threadIdx.x * SEL_ITEMS;
+            float v[SEL_ITEMS];
+            unsigned gt = 0, eq = 0;
+#pragma unroll
+            for (int u = 0; u < SEL_ITEMS; ++u) v[u] = (i0 + u < count) ? vals[i0 + u] : 0.f;
+#pragma unroll
+            for (int u = 0; u < SEL_ITEMS; ++u) {
+                if (i0 + u < count) {
+                    const uint32_t key = float_key(v[u]);
+                    gt |= (key > tkey ? 1u : 0u) << u;
+                    eq |= (key == tkey ? 1u : 0u) << u;
+                }
             }
-            int tot;
-            const int pos = block_excl_scan((gt ? 1 : 0) | (eq ? (1 << 16) : 0), wtot, tot);
-            const int pg = base_gt + (pos & 0xffff), pe = base_eq + (pos >> 16);
-            int slot = -1;
-            if (gt) slot = pg;
-            else if (eq && pe < need_eq) slot = n_gt + pe;
-            if (slot >= 0) {
-                cs[slot] = v;
-                ci[slot] = list ? list[idx] : idx;
+            if (__syncthreads_or((gt | eq) != 0)) {      // most chunks hold no candidate
+                int tot;
+                const int pos = block_excl_scan(__popc(gt) | (__popc(eq) << 16), wtot, tot);
+                int pg = base_gt + (pos & 0xffff), pe = base_eq + (pos >> 16);
+#pragma unroll
+                for (int u = 0; u < SEL_ITEMS; ++u) {
+                    int slot = -1;
+                    if (gt & (1u << u)) slot = pg++;
+                    else if (eq & (1u << u)) {
+                        if (pe < need_eq) slot = n_gt + pe;
+                        ++pe;
+                    }
+                    if (slot >= 0) {
+                        const int e = list ? list[i0 + u] : i0 + u;
+                        cs[slot] = v[u];
+                        ci[slot] = cid ? cid[e] : e;
+                    }
+                }
+                base_gt += tot & 0xffff;
+                base_eq += tot >> 16;
             }
-            base_gt += tot & 0xffff;
-            base_eq += tot >> 16;
         }
         __syncthreads();
         if (threadIdx.x < Kq) {
@@ -558,6 +806,8 @@ hipError_t launch_topk(const Problem& P, const Work& W, bool use_ctl, const floa
     A.ctl = use_ctl ? W.ctl : nullptr;
     A.list0 = W.list[0];
     A.list1 = W.list[1];
+    A.cid = W.cid;
+    A.cache_cap = W.cache_cap;
     A.vals = vals;
     A.N = P.N;
     A.K = K;

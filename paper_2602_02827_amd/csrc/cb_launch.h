@@ -29,6 +29,12 @@ struct Work {
     int32_t* pi;          // [nq][T]
     int32_t* chunk_doc;   // [nchunks+1] first document of each token chunk (dense kernel)
     int* flag;            // [64] error / scratch flags
+    // cell cache of queries whose active set has shrunk to <= cache_cap documents
+    int cache_cap;        // slots per query (0: caching off)
+    int TP;               // floats per slot: T rounded up to whole 16-column tiles
+    int32_t* cid;         // [nq][cache_cap] document id of a slot
+    float2* cstat;        // [nq][cache_cap] revealed sum / centred squares of a slot
+    float* ccell;         // [nq][cache_cap][TP] the slot's MaxSim cells
 };
 
 struct Trace {            // all null when tracing is off
@@ -57,6 +63,12 @@ hipError_t launch_init(const Problem& P, const Work& W, const Knobs& kn, int R, 
 // Reveal one batch for every active (query, doc) pair by gathering the documents.
 hipError_t launch_gather_reveal(const Problem& P, const Work& W, const RevealRound& rr,
                                 hipStream_t st);
+
+// The reveal of round rr for queries that fit the cell cache: all T cells of every active
+// document are computed once and cached; later rounds and the rescore read them back.
+hipError_t launch_gather_cells(const Problem& P, const Work& W, const RevealRound& rr,
+                               hipStream_t st);
+hipError_t launch_cached_score(const Problem& P, const Work& W, float* out, hipStream_t st);
 
 // Exact scores.  ctl == nullptr: all documents of every query, written by doc id into
 // `out` ([nq][N]); otherwise the current active set, written by list position.

@@ -243,6 +243,42 @@ def test_colbandit_gather_and_dense_first_round_agree(B, S, oracle_mod):
     assert torch.equal(r1["topk_ids"], r2["topk_ids"]) and torch.equal(r1["topk_scores"], r2["topk_scores"])
 
 
+def _same_run(r1, r2):
+    for f in ("count", "tau", "lcb", "ucb", "alive"):
+        np.testing.assert_array_equal(getattr(r1["trace"], f), getattr(r2["trace"], f))
+    assert torch.equal(r1["topk_ids"], r2["topk_ids"]) and torch.equal(r1["topk_scores"], r2["topk_scores"])
+    assert r1["stats"] == r2["stats"] or all(
+        {k: v for k, v in a.items() if k != "ms_total"} == {k: v for k, v in b.items() if k != "ms_total"}
+        for a, b in zip(r1["stats"], r2["stats"]))
+
+
+@pytest.mark.parametrize("alpha,Bsz,T", [(0.2, 4, 32), (1.0, 4, 32), (0.5, 3, 24), (0.2, 8, 40), (1.0, 16, 100)])
+def test_cell_cache_and_regather_give_identical_runs(B, S, alpha, Bsz, T):
+    """Caching a visited document's cells must not change a single decision or bit."""
+    rng = np.random.default_rng(T)
+    w = _custom(S, rng.integers(1, 120, 1500).tolist(), 4, T, 128, "bf16", 5)
+    r1 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, alpha, 0.01, 5, 3, B=Bsz, trace=True)
+    r2 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, alpha, 0.01, 5, 3, B=Bsz, trace=True,
+                          no_cell_cache=True)
+    torch.cuda.synchronize()
+    assert max(s["rounds"] for s in r1["stats"]) >= 2
+    _same_run(r1, r2)
+
+
+def test_active_sets_larger_than_the_cell_cache(B, S, oracle_mod):
+    """N above the cache capacity with a conservative radius: the first gathered rounds
+    run uncached and a query switches to its cache only once its active set fits."""
+    rng = np.random.default_rng(8)
+    w = _custom(S, rng.integers(2, 9, 40000).tolist(), 3, 32, 128, "bf16", 21)
+    r1 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 1.0, 0.01, 5, 1, trace=True)
+    r2 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 1.0, 0.01, 5, 1, trace=True, no_cell_cache=True)
+    torch.cuda.synchronize()
+    surv = [s["survivors"] for s in r1["stats"]]
+    assert any(len(x) > 2 and x[1] > 16384 for x in surv), surv     # really started above capacity
+    _same_run(r1, r2)
+    _run_colbandit_case(B, oracle_mod, w, 5, 5, 4, 1.0, seed=1)
+
+
 def test_colbandit_support_wider_than_default(B, S, oracle_mod):
     w = S.config(1, device="cuda", scale=0.02, nq=3)
     _run_colbandit_case(B, oracle_mod, w, 5, 5, 4, 0.2, a=-1.5, b=1.25)
