@@ -390,6 +390,8 @@ constexpr int SEL_THREADS = 1024;
 constexpr int SEL_WAVES = SEL_THREADS / 64;
 constexpr int SEL_ITEMS = 4;                       // consecutive entries per thread per chunk
 constexpr int SEL_CHUNK = SEL_THREADS * SEL_ITEMS;
+constexpr int SEL_SAMPLE = 16384;                 // strided sample behind the pre-filter
+constexpr int SEL_PREFILTER_MIN = 8 * SEL_SAMPLE;  // lists longer than this are pre-filtered
 
 // Exclusive scan of v over the block in thread order; returns the thread's offset and the
 // block total.  wtot: LDS int[SEL_WAVES].  Two barriers.
@@ -590,52 +592,76 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
         __syncthreads();
     }
 
-    auto key_of = [&](int idx) -> uint32_t {
-        const int e = in ? in[idx] : idx;
+    auto key_of = [&](const int32_t* l, int idx) -> uint32_t {
+        const int e = l ? l[idx] : idx;
         float lcb, ucb;
         const float2 st = stat[e];
         interval(st.x, st.y, n, T, kappa, a, b, lcb, ucb);
         return float_key(lcb);
     };
-    const uint32_t tkey = block_kth_largest(count, A.K, key_of, hist, pick);
-    const float tau = key_float(tkey);
-
     const size_t tro = ((size_t)(A.r - 1) * A.nq + q) * A.N;
-    int base = 0;
-    for (int start = 0; start < count; start += SEL_CHUNK) {
-        const int i0 = start + threadIdx.x * SEL_ITEMS;     // SEL_ITEMS consecutive entries
-        int e[SEL_ITEMS];
-        float2 st[SEL_ITEMS];
+    // Stable compaction of {entry of l[0..cnt) : UCB >= thr} into outl (outl may be l itself:
+    // a chunk is read completely before anything is written, and writes stay below the
+    // next chunk).  The trace takes every dropped entry, and the kept ones if trace_kept.
+    auto filter = [&](const int32_t* l, int cnt, int32_t* outl, float thr, bool trace_kept) -> int {
+        int base = 0;
+        for (int start = 0; start < cnt; start += SEL_CHUNK) {
+            const int i0 = start + threadIdx.x * SEL_ITEMS;     // SEL_ITEMS consecutive entries
+            int e[SEL_ITEMS];
+            float2 st[SEL_ITEMS];
 #pragma unroll
-        for (int u = 0; u < SEL_ITEMS; ++u) {
-            const int idx = i0 + u;
-            e[u] = idx < count ? (in ? in[idx] : idx) : 0;
-        }
+            for (int u = 0; u < SEL_ITEMS; ++u) {
+                const int idx = i0 + u;
+                e[u] = idx < cnt ? (l ? l[idx] : idx) : 0;
+            }
 #pragma unroll
-        for (int u = 0; u < SEL_ITEMS; ++u) st[u] = (i0 + u < count) ? stat[e[u]] : make_float2(0.f, 0.f);
-        unsigned keep = 0;
+            for (int u = 0; u < SEL_ITEMS; ++u)
+                st[u] = (i0 + u < cnt) ? stat[e[u]] : make_float2(0.f, 0.f);
+            unsigned keep = 0;
 #pragma unroll
-        for (int u = 0; u < SEL_ITEMS; ++u) {
-            if (i0 + u < count) {
-                float lcb, ucb;
-                interval(st[u].x, st[u].y, n, T, kappa, a, b, lcb, ucb);
-                const bool kp = ucb >= tau;
-                keep |= (kp ? 1u : 0u) << u;
-                if (A.tr_lcb) {
-                    const int id = slots ? cid[e[u]] : e[u];
-                    A.tr_lcb[tro + id] = lcb;
-                    A.tr_ucb[tro + id] = ucb;
-                    A.tr_alive[tro + id] = kp ? 1 : 0;
+            for (int u = 0; u < SEL_ITEMS; ++u) {
+                if (i0 + u < cnt) {
+                    float lcb, ucb;
+                    interval(st[u].x, st[u].y, n, T, kappa, a, b, lcb, ucb);
+                    const bool kp = ucb >= thr;
+                    keep |= (kp ? 1u : 0u) << u;
+                    if (A.tr_lcb && (trace_kept || !kp)) {
+                        const int id = slots ? cid[e[u]] : e[u];
+                        A.tr_lcb[tro + id] = lcb;
+                        A.tr_ucb[tro + id] = ucb;
+                        A.tr_alive[tro + id] = kp ? 1 : 0;
+                    }
                 }
             }
-        }
-        int total;
-        int pos = base + block_excl_scan(__popc(keep), wtot, total);
+            int total;
+            int pos = base + block_excl_scan(__popc(keep), wtot, total);
 #pragma unroll
-        for (int u = 0; u < SEL_ITEMS; ++u)
-            if (keep & (1u << u)) out[pos++] = e[u];
-        base += total;
+            for (int u = 0; u < SEL_ITEMS; ++u)
+                if (keep & (1u << u)) outl[pos++] = e[u];
+            base += total;
+        }
+        return base;
+    };
+
+    // Large active sets (the first round): a strided sample gives a threshold tau_lo that
+    // cannot exceed tau (the K-th largest of a subset is at most that of the whole set), so
+    // one streaming pass keeps the candidates {UCB >= tau_lo}, a superset of both the
+    // survivors and the K largest LCBs; the exact threshold and the prune then run on
+    // those few.
+    const int32_t* sel_in = in;
+    int sel_count = count;
+    if (count > SEL_PREFILTER_MIN) {
+        const int stride = count / SEL_SAMPLE;
+        auto key_s = [&](int j) -> uint32_t { return key_of(in, j * stride); };
+        const float tau_lo = key_float(block_kth_largest(SEL_SAMPLE, A.K, key_s, hist, pick));
+        sel_count = filter(in, count, out, tau_lo, false);
+        sel_in = out;
     }
+    auto key_sel = [&](int idx) -> uint32_t { return key_of(sel_in, idx); };
+    const uint32_t tkey = block_kth_largest(sel_count, A.K, key_sel, hist, pick);
+    const float tau = key_float(tkey);
+    const int base = filter(sel_in, sel_count, out, tau, true);
+
     if (threadIdx.x == 0) {
         QueryCtl nc;
         nc.count = base;
@@ -700,8 +726,8 @@ hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
 // =====================================================================================
 struct TopkArgs {
     const QueryCtl* ctl;   // nullptr: all N documents, vals indexed by id
-    const int32_t* list0;
-    const int32_t* list1;
+    int32_t* list0;        // the list that is not the query's current one doubles as scratch
+    int32_t* list1;        // for candidate positions of long inputs
     const int32_t* cid;
     int cache_cap;
     const float* vals;     // [nq][N]
@@ -721,45 +747,76 @@ __global__ __launch_bounds__(SEL_THREADS) void k_topk(TopkArgs A) {
     int count = (int)A.N;
     const int32_t* list = nullptr;
     const int32_t* cid = nullptr;
+    int32_t* scratch = A.list0 + (size_t)q * A.N;
     if (A.ctl) {
         const QueryCtl c = A.ctl[q];
         count = c.count;
-        if (!c.implicit) list = (c.cur ? A.list1 : A.list0) + (size_t)q * A.N;
+        if (!c.implicit) {
+            list = (c.cur ? A.list1 : A.list0) + (size_t)q * A.N;
+            scratch = (c.cur ? A.list0 : A.list1) + (size_t)q * A.N;
+        }
         if (c.mode == 1) cid = A.cid + (size_t)q * A.cache_cap;
     }
     const float* vals = A.vals + (size_t)q * A.N;
     const int Kq = A.K < count ? A.K : count;
     if (Kq > 0) {
-        auto key_of = [&](int idx) -> uint32_t { return float_key(vals[idx]); };
-        const uint32_t tkey = block_kth_largest(count, Kq, key_of, hist, pick);
+        // candidate positions: all of 0..count-1, or (long inputs) those whose value reaches
+        // the K-th largest value of a strided sample, which cannot exceed the true K-th
+        const int32_t* cand = nullptr;
+        int ncand = count;
+        if (count > SEL_PREFILTER_MIN) {
+            int32_t* tmp = scratch;
+            const int stride = count / SEL_SAMPLE;
+            auto key_s = [&](int j) -> uint32_t { return float_key(vals[j * stride]); };
+            const uint32_t lo = block_kth_largest(SEL_SAMPLE, Kq, key_s, hist, pick);
+            int base = 0;
+            for (int start = 0; start < count; start += SEL_CHUNK) {
+                const int i0 = start + threadIdx.x * SEL_ITEMS;
+                unsigned keep = 0;
+#pragma unroll
+                for (int u = 0; u < SEL_ITEMS; ++u)
+                    if (i0 + u < count && float_key(vals[i0 + u]) >= lo) keep |= 1u << u;
+                if (__syncthreads_or(keep != 0)) {
+                    int total;
+                    int pos = base + block_excl_scan(__popc(keep), wtot, total);
+#pragma unroll
+                    for (int u = 0; u < SEL_ITEMS; ++u)
+                        if (keep & (1u << u)) tmp[pos++] = i0 + u;
+                    base += total;
+                }
+            }
+            __syncthreads();
+            cand = tmp;
+            ncand = base;
+        }
+        auto key_of = [&](int j) -> uint32_t { return float_key(vals[cand ? cand[j] : j]); };
+        const uint32_t tkey = block_kth_largest(ncand, Kq, key_of, hist, pick);
         // how many are strictly above the K-th value
         int gt_local = 0;
-        for (int base = 0; base < count; base += SEL_CHUNK) {
-#pragma unroll
-            for (int u = 0; u < SEL_ITEMS; ++u) {
-                const int idx = base + u * SEL_THREADS + threadIdx.x;
-                if (idx < count) gt_local += float_key(vals[idx]) > tkey;
-            }
-        }
+        for (int j = threadIdx.x; j < ncand; j += SEL_THREADS) gt_local += key_of(j) > tkey;
         int n_gt;
         block_excl_scan(gt_local, wtot, n_gt);
         const int need_eq = Kq - n_gt;
         int base_gt = 0, base_eq = 0;
-        for (int start = 0; start < count; start += SEL_CHUNK) {
+        for (int start = 0; start < ncand; start += SEL_CHUNK) {
             const int i0 = start + threadIdx.x * SEL_ITEMS;
             float v[SEL_ITEMS];
+            int p[SEL_ITEMS];
             unsigned gt = 0, eq = 0;
 #pragma unroll
-            for (int u = 0; u < SEL_ITEMS; ++u) v[u] = (i0 + u < count) ? vals[i0 + u] : 0.f;
+            for (int u = 0; u < SEL_ITEMS; ++u) {
+                p[u] = (i0 + u < ncand) ? (cand ? cand[i0 + u] : i0 + u) : 0;
+                v[u] = (i0 + u < ncand) ? vals[p[u]] : 0.f;
+            }
 #pragma unroll
             for (int u = 0; u < SEL_ITEMS; ++u) {
-                if (i0 + u < count) {
+                if (i0 + u < ncand) {
                     const uint32_t key = float_key(v[u]);
                     gt |= (key > tkey ? 1u : 0u) << u;
                     eq |= (key == tkey ? 1u : 0u) << u;
                 }
             }
-            if (__syncthreads_or((gt | eq) != 0)) {      // most chunks hold no candidate
+            if (__syncthreads_or((gt | eq) != 0)) {      // most chunks hold no winner
                 int tot;
                 const int pos = block_excl_scan(__popc(gt) | (__popc(eq) << 16), wtot, tot);
                 int pg = base_gt + (pos & 0xffff), pe = base_eq + (pos >> 16);
@@ -772,7 +829,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_topk(TopkArgs A) {
                         ++pe;
                     }
                     if (slot >= 0) {
-                        const int e = list ? list[i0 + u] : i0 + u;
+                        const int e = list ? list[p[u]] : p[u];
                         cs[slot] = v[u];
                         ci[slot] = cid ? cid[e] : e;
                     }

@@ -279,6 +279,38 @@ def test_active_sets_larger_than_the_cell_cache(B, S, oracle_mod):
     _run_colbandit_case(B, oracle_mod, w, 5, 5, 4, 1.0, seed=1)
 
 
+@pytest.mark.parametrize("K", [5, 300])
+def test_long_lists_take_the_sampled_prefilter(B, S, oracle_mod, K):
+    """Lists far longer than the selection kernels' sample: the threshold of a strided sample
+    pre-filters candidates before the exact selection.  Checked against the oracle (rounds,
+    survivors, top-K) and against a full sort of the GPU's own scores."""
+    rng = np.random.default_rng(77)
+    w = _custom(S, rng.integers(1, 4, 150000).tolist(), 2, 32, 128, "bf16", 31)
+    full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K)
+    torch.cuda.synchronize()
+    sc = full["scores"].cpu().numpy()
+    for q in range(w.nq):
+        order = np.lexsort((np.arange(w.N), -sc[q]))[:K]
+        np.testing.assert_array_equal(full["topk_ids"][q].cpu().numpy(), order)
+        np.testing.assert_array_equal(full["topk_scores"][q].cpu().numpy(), sc[q][order])
+    _run_colbandit_case(B, oracle_mod, w, K, 5, 4, 0.2, seed=2)
+
+
+def test_long_lists_with_massive_ties(B, S):
+    """150,000 documents that are copies of 40 distinct ones: the K-th score is shared by
+    thousands; ties resolve to the lowest indices."""
+    base = _custom(S, [3] * 40, 2, 32, 128, "bf16", 13)
+    reps = 3750
+    docs = base.docs.repeat(reps, 1)
+    off = (torch.arange(40 * reps + 1, dtype=torch.int64) * 3).cuda()
+    r = B.colbandit_full_maxsim(base.Q, docs, off, K=100)
+    torch.cuda.synchronize()
+    sc = r["scores"].cpu().numpy()
+    for q in range(2):
+        order = np.lexsort((np.arange(40 * reps), -sc[q]))[:100]
+        np.testing.assert_array_equal(r["topk_ids"][q].cpu().numpy(), order)
+
+
 def test_colbandit_support_wider_than_default(B, S, oracle_mod):
     w = S.config(1, device="cuda", scale=0.02, nq=3)
     _run_colbandit_case(B, oracle_mod, w, 5, 5, 4, 0.2, a=-1.5, b=1.25)
