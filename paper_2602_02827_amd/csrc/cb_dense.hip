@@ -11,8 +11,8 @@
 //   * Query rows are the B operand and stay in registers for the whole kernel: each
 //     wavefront holds NT column tiles of 16 rows, full depth (NT*d/8 VGPRs).
 //   * Document tokens are the A operand.  They stream through a four-slot LDS ring of
-//     64-token stages (global -> registers -> LDS, two stages ahead of the reader), so a
-//     token is read from memory once per workgroup and from LDS once per wavefront.
+//     64-token stages (direct global -> LDS copies issued two stages ahead of the reader), so
+//     a token is read from memory once per workgroup and from LDS once per wavefront.
 //     Rows are stored with their 16-byte pieces XOR-swizzled by the row index, which
 //     spreads the 16 rows of an operand block over all banks.
 //   * Blocks of 16 tokens are aligned to the start of each document; a short last block
@@ -50,7 +50,6 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
     using F = Frag<bf16_tag, D>;
     constexpr int ROWB = D * 2;            // bytes per token row
     constexpr int NCH = ROWB / 16;         // 16-byte pieces per row
-    constexpr int LD_PER_THREAD = STAGE_ROWS * NCH / DENSE_THREADS;
     __shared__ __attribute__((aligned(16))) char ring[RING_ROWS * ROWB];
 
     const int lane = threadIdx.x & 63;
@@ -96,29 +95,30 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
         bq[tt].load((const char*)A.Q + ((size_t)q * A.T + trow) * ROWB, kg);
     }
 
-    // ---- stage loader: 64 rows x ROWB bytes, 16 bytes per thread per step
+    // ---- stage loader: 64 rows x ROWB bytes, copied global -> LDS without passing through
+    // registers (global_load_lds_dwordx4: every lane names its 16 global bytes, the wavefront's
+    // 64 pieces land in 1 KB of consecutive LDS).  One instruction fills 64/NCH ring rows; the
+    // lane at physical piece position p of LDS row r fetches the logical piece p ^ (r & (NCH-1)).
     const char* src = (const char*)A.docs + (size_t)tok_begin * ROWB;
-    u32x4_t stage_regs[LD_PER_THREAD];
+    constexpr int ROWS_PER_LOAD = 64 / NCH;
+    constexpr int LOADS_PER_WAVE = STAGE_ROWS / ROWS_PER_LOAD / 4;
     auto stage_fetch = [&](int s) {
 #pragma unroll
-        for (int i = 0; i < LD_PER_THREAD; ++i) {
-            const int x = i * DENSE_THREADS + threadIdx.x;
-            int row = s * STAGE_ROWS + x / NCH;
-            row = row < ntok ? row : ntok - 1;      // past the end: re-read the last row (never used)
-            stage_regs[i] = *(const u32x4_t*)(src + (size_t)row * ROWB + (x % NCH) * 16);
+        for (int i = 0; i < LOADS_PER_WAVE; ++i) {
+            const int rbase = s * STAGE_ROWS + (i * 4 + wave) * ROWS_PER_LOAD;   // wave-uniform
+            if (rbase < ntok) {
+                const int lrow = rbase + lane / NCH;                  // the LDS row this lane fills
+                const int grow = lrow < ntok ? lrow : ntok - 1;       // rows past the end are never read
+                const int c = (lane & (NCH - 1)) ^ (lrow & (NCH - 1));
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(src + (size_t)grow * ROWB + c * 16),
+                    (__attribute__((address_space(3))) void*)(ring + (rbase & (RING_ROWS - 1)) * ROWB),
+                    16, 0, 0);
+            }
         }
     };
-    auto stage_commit = [&](int s) {
-#pragma unroll
-        for (int i = 0; i < LD_PER_THREAD; ++i) {
-            const int x = i * DENSE_THREADS + threadIdx.x;
-            const int row = s * STAGE_ROWS + x / NCH;
-            const int ch = x % NCH;
-            if (row < ntok)
-                *(u32x4_t*)(ring + (row & (RING_ROWS - 1)) * ROWB + ((ch ^ (row & (NCH - 1))) * 16)) =
-                    stage_regs[i];
-        }
-    };
+    // the copies of a stage must have landed before the barrier that publishes it
+    auto stage_wait = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */ };
 
     // ---- document walk state (identical in all four wavefronts)
     int ibase = i0;
@@ -185,96 +185,86 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
     };
 
     // one block of 16 tokens against all NT column tiles
-    auto compute = [&](const F& a) {
-#pragma unroll
-        for (int tt = 0; tt < NT; ++tt) {
-            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-            F::mma(acc, a, bq[tt]);
-            h[tt] = fold_max(h[tt], acc);
-        }
-    };
-    // A fragment of the block whose lane row sits at ring byte offset `ro`; `co` are the
-    // lane's swizzled piece offsets
-    auto load_a = [&](F& a, int ro, const int (&co)[F::KS]) {
-#pragma unroll
-        for (int ks = 0; ks < F::KS; ++ks) a.v[ks] = *(const bf16x8_t*)(ring + ro + co[ks]);
-    };
-    constexpr int RING_BYTES = RING_ROWS * ROWB;
-    constexpr int BLOCK_BYTES = 16 * ROWB;
-
+    auto compute = [&](const F& a) { block_mma<NT>(a, bq, h); };
+    // ---- stage bookkeeping.  `published` stages are visible to every wavefront, stage
+    // `published` (if any) is in flight.  All four wavefronts walk the same documents and
+    // blocks, so they call stage_advance at the same points and its barrier matches up.
+    // Slot safety: when stage P starts to load into slot P & 3, no block can still need a
+    // row of stage P - 4 (the reader is at most 15 rows behind stage P - 2).
     const int nst = (ntok + STAGE_ROWS - 1) / STAGE_ROWS;
     stage_fetch(0);
-    stage_commit(0);
-    if (nst > 1) {
-        stage_fetch(1);
-        stage_commit(1);
-    }
+    if (nst > 1) stage_fetch(1);
+    stage_wait();
     __syncthreads();
-
-    int doc = i0 - 1;      // current document; its tokens are [.., dend) relative to tok_begin
-    int dend = 0, cur = 0;
-    bool started = false, finished = false;
-
-#pragma unroll 1
-    for (int s = 0; s < nst; ++s) {
-        const bool more = s + 2 < nst;
-        if (more) stage_fetch(s + 2);
-        const int avail = (s == nst - 1) ? ntok : (s + 1) * STAGE_ROWS;
-        while (!finished) {
-            if (cur >= dend) {
-                if (started) finalize(doc);
-                ++doc;
-                if (doc >= i1) {
-                    finished = true;
-                    break;
-                }
-                started = true;
-                cur = dend;
-                dend = rel_off(doc + 1);
-                continue;
-            }
-            // blocks of this document that are complete in the ring: n full ones, and the
-            // short last one if the document ends inside what has arrived
-            const int lim = dend < avail ? dend : avail;
-            int n = (lim - cur) >> 4;
-            const bool tail = dend <= avail && ((dend - cur) & 15) != 0;
-            if (n == 0 && !tail) break;
-            const int row0 = cur + col;
-            const int sw = row0 & (NCH - 1);          // blocks step by 16 rows: sw is invariant
-            int co[F::KS];
-#pragma unroll
-            for (int ks = 0; ks < F::KS; ++ks) co[ks] = ((ks * 4 + kg) ^ sw) * 16;
-            int ro = (row0 & (RING_ROWS - 1)) * ROWB;
-            cur += n * 16;
-            if (n > 0) {
-                F a0, a1;
-                load_a(a0, ro, co);
-                while (n >= 2) {                       // two blocks per trip, loads one ahead
-                    load_a(a1, (ro + BLOCK_BYTES) & (RING_BYTES - 1), co);
-                    compute(a0);
-                    ro = (ro + 2 * BLOCK_BYTES) & (RING_BYTES - 1);
-                    if (n > 2) load_a(a0, ro, co);
-                    compute(a1);
-                    n -= 2;
-                }
-                if (n == 1) compute(a0);
-            }
-            if (tail) {                                // rows past the end repeat the last token
-                int row = cur + col;
-                row = row < dend ? row : dend - 1;
-                const int swt = row & (NCH - 1);
-                const int rot = (row & (RING_ROWS - 1)) * ROWB;
-                F a;
-#pragma unroll
-                for (int ks = 0; ks < F::KS; ++ks)
-                    a.v[ks] = *(const bf16x8_t*)(ring + rot + (((ks * 4 + kg) ^ swt) * 16));
-                compute(a);
-                cur = dend;
-            }
-        }
-        if (more) stage_commit(s + 2);
+    int published = nst < 2 ? nst : 2;
+    if (published < nst) stage_fetch(published);
+    int avail = published * STAGE_ROWS < ntok ? published * STAGE_ROWS : ntok;
+    auto stage_advance = [&]() {
+        stage_wait();
         __syncthreads();
+        ++published;
+        if (published < nst) stage_fetch(published);
+        avail = published * STAGE_ROWS < ntok ? published * STAGE_ROWS : ntok;
+    };
+
+    // ---- block stream: the load cursor walks documents and their 16-token blocks and
+    // issues each block's A-operand reads one block ahead of the MFMAs that use them.
+    int ldoc = i0 - 1, lend = 0, lcur = 0;      // load cursor: document, its end, next row
+    struct BlockInfo {
+        int doc;       // document the block belongs to (-1: no block, stream exhausted)
+        bool last;     // last block of its document
+    };
+    auto next_block = [&](F& a) -> BlockInfo {
+        while (lcur >= lend) {                  // next document (empty ones yield no block)
+            ++ldoc;
+            if (ldoc >= i1) return BlockInfo{-1, false};
+            lcur = lend;
+            lend = rel_off(ldoc + 1);
+        }
+        const int start = lcur;
+        const int end = start + 16 < lend ? start + 16 : lend;
+        while (end > avail) stage_advance();    // end <= ntok, so this stops at the last stage
+        // Lane -> row: any one-to-one assignment works (the max runs over all 16 rows).  LDS
+        // serves a 16-byte read per lane fastest when lanes 2j and 2j+1 hit an aligned pair of
+        // pieces; with the row-keyed swizzle that means an aligned row pair, so on an odd block
+        // start lane 0 takes the block's last row.  A short last block repeats the document's
+        // last token in the lanes past its end (a duplicate cannot change a max).
+        int row = (start & 1) ? ((col == 0) ? start + 15 : start - 1 + col) : start + col;
+        row = row < end ? row : end - 1;
+        const char* rp = ring + (row & (RING_ROWS - 1)) * ROWB;
+        const int sw = row & (NCH - 1);
+#pragma unroll
+        for (int ks = 0; ks < F::KS; ++ks)
+            a.v[ks] = *(const bf16x8_t*)(rp + (((ks * 4 + kg) ^ sw) * 16));
+        lcur = end;
+        return BlockInfo{ldoc, end == lend};
+    };
+
+    // ---- consumer: MFMAs of block k overlap the operand reads of block k+1; a document's
+    // epilogue runs after its last block.  Documents without tokens (a precondition
+    // violation) still get their -inf result.
+    int done_doc = i0 - 1;                      // documents < = done_doc have been finalized
+    auto retire = [&](const BlockInfo& b) {
+        if (b.last) {
+            while (done_doc + 1 < b.doc) finalize(++done_doc);   // empty documents in between
+            finalize(b.doc);
+            done_doc = b.doc;
+        }
+    };
+    F a0, a1;
+    BlockInfo b0 = next_block(a0), b1;
+    while (b0.doc >= 0) {
+        b1 = next_block(a1);
+        __builtin_amdgcn_sched_barrier(0);      // keep the reads of the next block up here
+        compute(a0);
+        retire(b0);
+        if (b1.doc < 0) break;
+        b0 = next_block(a0);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(a1);
+        retire(b1);
     }
+    while (done_doc + 1 < i1) finalize(++done_doc);             // trailing empty documents
 }
 
 // ---- first document of every token chunk: chunk_doc[c] = min{ i : off[i] >= c*C }

@@ -58,6 +58,15 @@ template <int D> struct Frag<bf16_tag, D> {
         for (int s = 0; s < KS; ++s)
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v[s], b.v[s], acc, 0, 0, 0);
     }
+    // two independent accumulation chains, interleaved step by step
+    __device__ __forceinline__ static void mma2(f32x4_t& c0, f32x4_t& c1, const Frag& a,
+                                                const Frag& b0, const Frag& b1) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            c0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v[s], b0.v[s], c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v[s], b1.v[s], c1, 0, 0, 0);
+        }
+    }
 };
 
 template <int D> struct Frag<f32_tag, D> {
@@ -77,6 +86,17 @@ template <int D> struct Frag<f32_tag, D> {
                 acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[j][e], b.v[j][e], acc, 0, 0, 0);
         }
     }
+    __device__ __forceinline__ static void mma2(f32x4_t& c0, f32x4_t& c1, const Frag& a,
+                                                const Frag& b0, const Frag& b1) {
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                c0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[j][e], b0.v[j][e], c0, 0, 0, 0);
+                c1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[j][e], b1.v[j][e], c1, 0, 0, 0);
+            }
+        }
+    }
 };
 
 // Accumulator layout of the 16x16 MFMAs: lane holds column (lane & 15) and rows
@@ -88,6 +108,34 @@ __device__ __forceinline__ float max4(const f32x4_t& c) {
 __device__ __forceinline__ float fold_max(float h, const f32x4_t& c) {
     const float t = fmaxf(fmaxf(c[0], c[1]), c[2]);
     return fmaxf(fmaxf(h, t), c[3]);
+}
+
+// One block of 16 document tokens against NT column tiles, folded into the running
+// maxima h.  Tiles go in pairs: the two accumulation chains of a pair are interleaved
+// (no back-to-back dependent MFMAs) and a pair's maxima are taken while the next pair's
+// MFMAs run.
+template <int NT, class F>
+__device__ __forceinline__ void block_mma(const F& a, const F (&bq)[NT], float (&h)[NT]) {
+    if constexpr (NT == 1) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        F::mma(acc, a, bq[0]);
+        h[0] = fold_max(h[0], acc);
+    } else {
+        f32x4_t p0 = {0.f, 0.f, 0.f, 0.f}, p1 = p0;
+#pragma unroll
+        for (int p = 0; p < NT / 2; ++p) {
+            f32x4_t c0 = {0.f, 0.f, 0.f, 0.f}, c1 = c0;
+            F::mma2(c0, c1, a, bq[2 * p], bq[2 * p + 1]);
+            if (p > 0) {
+                h[2 * p - 2] = fold_max(h[2 * p - 2], p0);
+                h[2 * p - 1] = fold_max(h[2 * p - 1], p1);
+            }
+            p0 = c0;
+            p1 = c1;
+        }
+        h[NT - 2] = fold_max(h[NT - 2], p0);
+        h[NT - 1] = fold_max(h[NT - 1], p1);
+    }
 }
 
 // ---------------------------------------------------------------------------------
