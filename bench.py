@@ -25,6 +25,13 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the dense Full-MaxSim kernel on the default workload, from the two
+# counter runs summarised in profiles/k_dense_C3_hbm_traffic.md (FETCH_SIZE + WRITE_SIZE, each
+# scaled by the same counter's reading for the 1 GiB calibration copy below).  Reported only
+# when the run is that workload.
+MEASURED_TRAFFIC_BYTES = {}
+CALIBRATION_COPY_BYTES = 1 << 30
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -67,8 +74,17 @@ def main():
     out_cb = {"topk_ids": torch.empty((nq, K), dtype=torch.int64, device=dev),
               "topk_scores": torch.empty((nq, K), dtype=torch.float32, device=dev)}
 
-    def run_full():
-        return B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K, workspace=ws, out=out_full)
+    # a plain copy kernel of known size (reads 1 GiB, writes 1 GiB): the yardstick that the
+    # hardware-counter runs use to turn FETCH_SIZE / WRITE_SIZE readings into bytes
+    cal_src = torch.ones(CALIBRATION_COPY_BYTES // 4, dtype=torch.float32, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    torch.mul(cal_src, 1.0, out=cal_dst)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
+    def run_full(phases=False):
+        return B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K, workspace=ws, out=out_full,
+                                       want_phase_ms=phases)
 
     def run_cb(stats=False):
         return B.colbandit_topk(w.Q, w.docs, w.offsets, K, alpha, delta, M, w.seed, workspace=ws,
@@ -82,9 +98,10 @@ def main():
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    ms_kernel = []
     for s in range(args.steps):
         ev[s][0].record()
-        run_full()
+        ms_kernel.append(run_full(phases=True)["phase_ms"])   # events on the launch stream
         ev[s][1].record()
         run_cb()
         ev[s][2].record()
@@ -115,15 +132,28 @@ def main():
 
     flops_full = 2.0 * nq * T * d * total
     tflops = flops_full / (ms_full * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_dense (Full-MaxSim, bf16 16x16x32 MFMA)",
-                "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                "note": "algorithmic flops 2*nq*T*d*tokens per launch over the event-timed "
-                        "colbandit_full_maxsim call (dense kernel + chunk table + top-K kernels)"}
+    ms_dense = float(np.mean([m[0] for m in ms_kernel]))
+    ms_topk = float(np.mean([m[1] for m in ms_kernel]))
+    tflops_kernel = flops_full / (ms_dense * 1e-3) / 1e12
+    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, nq, N, total))
+    dense = w.dtype == "bf16"
+    roofline = {"bound": "mfma" if dense else "alu",
+                "kernel": "k_dense (Full-MaxSim scoring kernel, bf16 16x16x32 MFMA)" if dense
+                          else "k_gather (fp32 inputs)",
+                "achieved": round(tflops_kernel, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(tflops_kernel / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                "ms_per_launch": round(ms_dense, 3),
+                "flops_per_launch": flops_full,
+                "note": "algorithmic flops 2*T*d per (query, document token) x nq x tokens per "
+                        "launch, over the kernel's own duration taken by the library with "
+                        "events on the launch stream inside the timed steps; the whole call "
+                        "(kernel + chunk table + top-K, %.3f ms) runs at %.1f TFLOP/s"
+                        % (ms_full, tflops)}
 
     line = {
-        "metric": "queries/s through Full-MaxSim top-K + Col-Bandit top-K (N=%d, T=%d, d=%d, K=%d)"
-                  % (N, T, d, K),
+        "metric": "queries/s through one step = Full-MaxSim top-K + Col-Bandit top-K at N=%d,T=%d,"
+                  "d=%d,K=%d (MaxSim cells/s and Overlap@%d vs exhaustive in full_maxsim / "
+                  "colbandit)" % (N, T, d, K, K),
         "value": round(nq / (ms_step * 1e-3), 2), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -132,7 +162,8 @@ def main():
                    "total_tokens": total, "K": K, "alpha_ef": alpha, "delta": delta, "M": M, "B": w.B},
         "full_maxsim": {"ms": round(ms_full, 3), "queries_per_s": round(nq / (ms_full * 1e-3), 1),
                         "cells_per_s": round(cells_total / (ms_full * 1e-3), 1),
-                        "tflops": round(tflops, 2)},
+                        "tflops": round(tflops, 2), "ms_scoring_kernel": round(ms_dense, 3),
+                        "ms_topk": round(ms_topk, 3)},
         "colbandit": {"ms": round(ms_cb, 3), "queries_per_s": round(nq / (ms_cb * 1e-3), 1),
                       "revealed_cells_per_s": round(cells_touched / (ms_cb * 1e-3), 1),
                       "effective_cells_per_s": round(cells_total / (ms_cb * 1e-3), 1),
@@ -141,6 +172,9 @@ def main():
                       "mean_survivors_after_round1": round(surv1, 1),
                       "mean_survivors_by_round": surv_by_round,
                       "speedup_vs_full": round(ms_full / ms_cb, 2),
+                      "ms_phases": {k[3:]: round(st[0][k], 3) for k in
+                                    ("ms_first_reveal", "ms_later_reveals", "ms_select_prune",
+                                     "ms_rescore_topk")},
                       "survivor_scores_bit_identical_to_full": same_bits},
         "roofline": roofline,
         "paper_context": "paper (CPU, real embeddings): up to ~8x fewer MaxSim FLOPs, up to ~13x "

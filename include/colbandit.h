@@ -96,7 +96,18 @@ typedef struct {
     int64_t cells_unique;                             /* |Omega| with set semantics    */
     float ms_total;                                   /* device time of the whole call
                                                          (all queries of the batch)    */
+    float ms_first_reveal;                            /* of which: reveal of round 1   */
+    float ms_later_reveals;                           /* reveals of rounds >= 2        */
+    float ms_select_prune;                            /* thresholds and pruning        */
+    float ms_rescore_topk;                            /* rescore and final top-K
+                                                         (cf. the paper's stage split in
+                                                         its overhead-breakdown table)  */
 } colbandit_stats;
+
+/* sizeof(colbandit_opts) / sizeof(colbandit_stats) as this library was compiled: lets a
+ * binding written in another language check its own struct definitions. */
+size_t colbandit_sizeof_opts(void);
+size_t colbandit_sizeof_stats(void);
 
 /*
  * Trace buffer layout (R = ceil(T/B) rounds, nq = n_queries), in this order:
@@ -123,15 +134,21 @@ size_t colbandit_workspace_bytes(int n_queries, int T, int d, int64_t N,
  *                                required when K > 0
  *   cells                        DEVICE float [n_queries][N][T] or NULL: the MaxSim
  *                                matrix itself (test aid)
+ *   phase_ms                     HOST float [2] or NULL.  When non-NULL the call
+ *                                synchronises the stream before returning and writes
+ *                                the device time of the scoring kernel alone
+ *                                (phase_ms[0]) and of the top-K selection
+ *                                (phase_ms[1]), in milliseconds, taken with events
+ *                                on `stream`
  *   workspace                    DEVICE, 256-byte aligned, >= colbandit_workspace_bytes
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; fp32 inputs
- * use fp32 matrix instructions.  Fully asynchronous.
+ * use fp32 matrix instructions.  Fully asynchronous unless phase_ms is given.
  */
 int colbandit_full_maxsim(const void *Q, int n_queries, int T, int d, colbandit_dtype dt,
                           const void *doc_tokens, const int64_t *doc_offsets, int64_t N,
                           int64_t total_tokens, int K, float *scores, int64_t *topk_ids,
-                          float *topk_scores, float *cells, void *workspace,
-                          size_t workspace_bytes, void *stream);
+                          float *topk_scores, float *cells, float *phase_ms,
+                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Col-Bandit top-K (Algorithm 1).

@@ -22,7 +22,8 @@ MAX_ROUNDS = 64
 EXPORTS = [
     "colbandit_full_maxsim", "colbandit_topk", "colbandit_workspace_bytes",
     "colbandit_trace_bytes", "colbandit_permutation", "colbandit_radius_prefactor",
-    "colbandit_validate_offsets", "colbandit_strerror",
+    "colbandit_validate_offsets", "colbandit_strerror", "colbandit_sizeof_opts",
+    "colbandit_sizeof_stats",
 ]
 
 
@@ -36,7 +37,9 @@ class ColbanditOpts(ctypes.Structure):
 class ColbanditStats(ctypes.Structure):
     _fields_ = [("rounds", ctypes.c_int32), ("survivors", ctypes.c_int32 * (MAX_ROUNDS + 2)),
                 ("cells_elim", ctypes.c_int64), ("cells_rescore", ctypes.c_int64),
-                ("cells_unique", ctypes.c_int64), ("ms_total", ctypes.c_float)]
+                ("cells_unique", ctypes.c_int64), ("ms_total", ctypes.c_float),
+                ("ms_first_reveal", ctypes.c_float), ("ms_later_reveals", ctypes.c_float),
+                ("ms_select_prune", ctypes.c_float), ("ms_rescore_topk", ctypes.c_float)]
 
 
 class ColbanditError(RuntimeError):
@@ -60,7 +63,7 @@ def lib():
         vp, i, i64, sz, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float
         L.colbandit_full_maxsim.restype = i
         L.colbandit_full_maxsim.argtypes = [vp, i, i, i, i, vp, vp, i64, i64, i, vp, vp, vp, vp,
-                                            vp, sz, vp]
+                                            ctypes.POINTER(ctypes.c_float), vp, sz, vp]
         L.colbandit_topk.restype = i
         L.colbandit_topk.argtypes = [vp, i, i, i, i, vp, vp, i64, i64, i, f, f, i, ctypes.c_uint64,
                                      ctypes.POINTER(ColbanditOpts), vp, vp,
@@ -75,6 +78,13 @@ def lib():
         L.colbandit_radius_prefactor.argtypes = [f, f, i, i64, i]
         L.colbandit_validate_offsets.restype = i
         L.colbandit_validate_offsets.argtypes = [vp, i64, i64, vp, sz, vp]
+        L.colbandit_sizeof_opts.restype = sz
+        L.colbandit_sizeof_opts.argtypes = []
+        L.colbandit_sizeof_stats.restype = sz
+        L.colbandit_sizeof_stats.argtypes = []
+        if (L.colbandit_sizeof_opts() != ctypes.sizeof(ColbanditOpts)
+                or L.colbandit_sizeof_stats() != ctypes.sizeof(ColbanditStats)):
+            raise ImportError("libcolbandit.so was built from a different colbandit.h: rebuild it")
         L.colbandit_strerror.restype = ctypes.c_char_p
         L.colbandit_strerror.argtypes = [i]
         _lib = L
@@ -144,8 +154,10 @@ def colbandit_validate_offsets(offsets: torch.Tensor, total_tokens: int, workspa
 
 
 def colbandit_full_maxsim(Q, docs, offsets, K=0, want_scores=True, want_cells=False,
-                          workspace=None, out=None):
-    """Exhaustive scoring.  Returns dict(scores [nq,N] | None, topk_ids, topk_scores, cells)."""
+                          workspace=None, out=None, want_phase_ms=False):
+    """Exhaustive scoring.  Returns dict(scores [nq,N] | None, topk_ids, topk_scores, cells,
+    phase_ms).  `want_phase_ms` makes the call synchronous and returns (scoring kernel ms,
+    top-K ms) measured by the library with events on the launch stream."""
     Q, nq, T, d, N, total = _shapes(Q, docs, offsets)
     dev = docs.device
     ws = workspace if workspace is not None else new_workspace(nq, T, d, N, total, dev)
@@ -160,12 +172,14 @@ def colbandit_full_maxsim(Q, docs, offsets, K=0, want_scores=True, want_cells=Fa
         sc = o.get("topk_scores") if o.get("topk_scores") is not None else \
             torch.empty((nq, K), dtype=torch.float32, device=dev)
     cells = torch.empty((nq, N, T), dtype=torch.float32, device=dev) if want_cells else None
+    phase = (ctypes.c_float * 2)() if want_phase_ms else None
     rc = lib().colbandit_full_maxsim(_ptr(Q), nq, T, d, _dt(Q), _ptr(docs), _ptr(offsets), N, total,
-                                     K, _ptr(scores), _ptr(ids), _ptr(sc), _ptr(cells), _ptr(ws),
-                                     ws.numel(), _stream())
+                                     K, _ptr(scores), _ptr(ids), _ptr(sc), _ptr(cells), phase,
+                                     _ptr(ws), ws.numel(), _stream())
     if rc:
         raise ColbanditError(rc, "colbandit_full_maxsim")
-    return {"scores": scores, "topk_ids": ids, "topk_scores": sc, "cells": cells}
+    return {"scores": scores, "topk_ids": ids, "topk_scores": sc, "cells": cells,
+            "phase_ms": (phase[0], phase[1]) if want_phase_ms else None}
 
 
 @dataclass
@@ -177,24 +191,32 @@ class Trace:
     alive: np.ndarray    # bool
 
 
-def _parse_trace(buf: torch.Tensor, nq, T, B, N) -> Trace:
+def _parse_trace(buf: torch.Tensor, nq, T, B, N, queries=None) -> Trace:
+    """Splits the device trace buffer; `queries` keeps only those query columns (in that order)."""
     R = (T + B - 1) // B
-    raw = buf.cpu().numpy()
     al = lambda x: (x + 255) // 256 * 256
+    qs = list(range(nq)) if queries is None else list(queries)
+    qi = torch.as_tensor(qs, dtype=torch.int64, device=buf.device)
+
+    def part(o, nbytes, dtype, shape):
+        t = buf[o:o + nbytes].view(dtype).view(shape)
+        return t.index_select(1, qi).cpu().numpy()
+
     o = 0
-    count = raw[o:o + 4 * (R + 1) * nq].view(np.int32).reshape(R + 1, nq).copy(); o += al(4 * (R + 1) * nq)
-    tau = raw[o:o + 4 * R * nq].view(np.float32).reshape(R, nq).copy(); o += al(4 * R * nq)
-    lcb = raw[o:o + 4 * R * nq * N].view(np.float32).reshape(R, nq, N).copy(); o += al(4 * R * nq * N)
-    ucb = raw[o:o + 4 * R * nq * N].view(np.float32).reshape(R, nq, N).copy(); o += al(4 * R * nq * N)
-    alive = raw[o:o + R * nq * N].reshape(R, nq, N).astype(bool)
+    count = part(o, 4 * (R + 1) * nq, torch.int32, (R + 1, nq)); o += al(4 * (R + 1) * nq)
+    tau = part(o, 4 * R * nq, torch.float32, (R, nq)); o += al(4 * R * nq)
+    lcb = part(o, 4 * R * nq * N, torch.float32, (R, nq, N)); o += al(4 * R * nq * N)
+    ucb = part(o, 4 * R * nq * N, torch.float32, (R, nq, N)); o += al(4 * R * nq * N)
+    alive = part(o, R * nq * N, torch.uint8, (R, nq, N)).astype(bool)
     return Trace(count, tau, lcb, ucb, alive)
 
 
 def colbandit_topk(Q, docs, offsets, K, alpha_ef=0.2, delta=0.01, M=5, seed=0, B=0, a=0.0, b=0.0,
                    pi=None, trace=False, force_gather=False, want_stats=True, workspace=None,
-                   out=None, no_cell_cache=False):
+                   out=None, no_cell_cache=False, trace_queries=None):
     """Col-Bandit top-K.  Returns dict(topk_ids, topk_scores, stats (list of dict) | None,
-    trace (Trace) | None).  `pi`: optional int32 device tensor [nq,T]."""
+    trace (Trace) | None).  `pi`: optional int32 device tensor [nq,T]; `trace_queries`: keep
+    only these queries' columns of the trace (the device buffer still covers all of them)."""
     Q, nq, T, d, N, total = _shapes(Q, docs, offsets)
     dev = docs.device
     ws = workspace if workspace is not None else new_workspace(nq, T, d, N, total, dev)
@@ -226,9 +248,12 @@ def colbandit_topk(Q, docs, offsets, K, alpha_ef=0.2, delta=0.01, M=5, seed=0, B
     if stats is not None:
         st = [{"rounds": s.rounds, "survivors": list(s.survivors[: s.rounds + 1]),
                "cells_elim": s.cells_elim, "cells_rescore": s.cells_rescore,
-               "cells_unique": s.cells_unique, "ms_total": s.ms_total} for s in stats]
+               "cells_unique": s.cells_unique, "ms_total": s.ms_total,
+               "ms_first_reveal": s.ms_first_reveal, "ms_later_reveals": s.ms_later_reveals,
+               "ms_select_prune": s.ms_select_prune, "ms_rescore_topk": s.ms_rescore_topk}
+              for s in stats]
     tr = None
     if trace:
         torch.cuda.synchronize()
-        tr = _parse_trace(tbuf, nq, T, Beff, N)
+        tr = _parse_trace(tbuf, nq, T, Beff, N, trace_queries)
     return {"topk_ids": ids, "topk_scores": sc, "stats": st, "trace": tr}

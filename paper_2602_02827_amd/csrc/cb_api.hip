@@ -99,6 +99,45 @@ int check_workspace(const void* ws, size_t bytes, size_t need) {
     return COLBANDIT_OK;
 }
 
+// Phase timing for colbandit_stats: one HIP event per phase boundary on the call's stream.
+enum { PH_FIRST_REVEAL = 0, PH_LATER_REVEAL = 1, PH_SELECT = 2, PH_RESCORE = 3, PH_COUNT = 4 };
+struct PhaseTimer {
+    static constexpr int kMax = 4 * (COLBANDIT_MAX_ROUNDS + 4);
+    hipEvent_t ev[kMax];
+    int phase[kMax];       // phase that ENDS at event i (event 0 is the start)
+    int n = 0;
+    bool on = false;
+    hipStream_t st = nullptr;
+    bool start(hipStream_t s) {
+        on = true;
+        st = s;
+        return mark(-1);
+    }
+    bool mark(int ph) {
+        if (!on) return true;
+        if (n >= kMax) return true;
+        if (hipEventCreate(&ev[n]) != hipSuccess) return false;
+        phase[n] = ph;
+        (void)hipEventRecord(ev[n], st);
+        ++n;
+        return true;
+    }
+    void collect(float (&ms)[PH_COUNT], float& total) {      // after the stream was synchronised
+        for (int i = 0; i < PH_COUNT; ++i) ms[i] = 0.f;
+        total = 0.f;
+        for (int i = 1; i < n; ++i) {
+            float t = 0.f;
+            (void)hipEventElapsedTime(&t, ev[i - 1], ev[i]);
+            if (phase[i] >= 0) ms[phase[i]] += t;
+            total += t;
+        }
+    }
+    void destroy() {
+        for (int i = 0; i < n; ++i) (void)hipEventDestroy(ev[i]);
+        n = 0;
+    }
+};
+
 double rho_n(int n, int T) {
     // finite-population correction, Appendix A
     if (2 * n <= T) return 1.0 - (double)(n - 1) / (double)T;
@@ -180,10 +219,13 @@ int colbandit_validate_offsets(const int64_t* doc_offsets, int64_t N, int64_t to
     return h ? COLBANDIT_ERR_BAD_OFFSETS : COLBANDIT_OK;
 }
 
+size_t colbandit_sizeof_opts(void) { return sizeof(colbandit_opts); }
+size_t colbandit_sizeof_stats(void) { return sizeof(colbandit_stats); }
+
 int colbandit_full_maxsim(const void* Q, int n_queries, int T, int d, colbandit_dtype dt,
                           const void* doc_tokens, const int64_t* doc_offsets, int64_t N,
                           int64_t total_tokens, int K, float* scores, int64_t* topk_ids,
-                          float* topk_scores, float* cells, void* workspace,
+                          float* topk_scores, float* cells, float* phase_ms, void* workspace,
                           size_t workspace_bytes, void* stream) {
     int rc = check_shapes(Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens);
     if (rc) return rc;
@@ -200,15 +242,37 @@ int colbandit_full_maxsim(const void* Q, int n_queries, int T, int d, colbandit_
     hipStream_t st = (hipStream_t)stream;
     float* out = scores ? scores : W.scores;
 
-    hipError_t e;
+    // phase_ms: event 0 | chunk table | event 1 | scoring kernel | event 2 | top-K | event 3
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    int n_ev = 0;
+    auto mark = [&]() {
+        if (phase_ms && n_ev < 4 && hipEventCreate(&ev[n_ev]) == hipSuccess) (void)hipEventRecord(ev[n_ev++], st);
+    };
+    hipError_t e = hipSuccess;
+    mark();
     if (dense_supported(P)) {
         int n_chunks = 0;
         e = launch_dense_prepare(P, W, kChunkTokens, &n_chunks, st);
+        mark();
         if (e == hipSuccess) e = launch_dense_score(P, W, kChunkTokens, n_chunks, out, cells, st);
     } else {
+        mark();
         e = launch_gather_score(P, W, false, out, cells, st);
     }
+    mark();
     if (e == hipSuccess && K > 0) e = launch_topk(P, W, false, out, K, topk_ids, topk_scores, st);
+    mark();
+    if (phase_ms) {
+        phase_ms[0] = phase_ms[1] = 0.f;
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e == hipSuccess && n_ev == 4) {
+            (void)hipEventElapsedTime(&phase_ms[0], ev[1], ev[2]);
+            (void)hipEventElapsedTime(&phase_ms[1], ev[2], ev[3]);
+        } else if (e == hipSuccess) {
+            e = hipErrorUnknown;
+        }
+        for (int i = 0; i < n_ev; ++i) (void)hipEventDestroy(ev[i]);
+    }
     return e == hipSuccess ? COLBANDIT_OK : COLBANDIT_ERR_HIP;
 }
 
@@ -273,12 +337,8 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
     const Problem P{Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens};
     hipStream_t st = (hipStream_t)stream;
 
-    hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    if (stats) {
-        if (hipEventCreate(&ev0) != hipSuccess || hipEventCreate(&ev1) != hipSuccess)
-            return COLBANDIT_ERR_HIP;
-        (void)hipEventRecord(ev0, st);
-    }
+    PhaseTimer pt;
+    if (stats && !pt.start(st)) return COLBANDIT_ERR_HIP;
 
     hipError_t e = launch_init(P, W, kn, R, seed, user_pi, tr, st);
     const bool loop = N > (int64_t)K + M;    // |A_1| > K + M, else the loop body never runs
@@ -302,28 +362,29 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
             e = launch_gather_reveal(P, W, rr, st);
             if (e == hipSuccess && r >= 2) e = launch_gather_cells(P, W, rr, st);
         }
+        pt.mark(r == 1 ? PH_FIRST_REVEAL : PH_LATER_REVEAL);
         if (e == hipSuccess) e = launch_select_prune(P, W, kn, rr, tr, st);
+        pt.mark(PH_SELECT);
     }
     if (e == hipSuccess) e = launch_gather_score(P, W, true, W.rescored, nullptr, st);
     if (e == hipSuccess) e = launch_cached_score(P, W, W.rescored, st);
     if (e == hipSuccess) e = launch_topk(P, W, true, W.rescored, K, topk_ids, topk_scores, st);
+    pt.mark(PH_RESCORE);
     if (e != hipSuccess) {
-        if (stats) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); }
+        pt.destroy();
         return COLBANDIT_ERR_HIP;
     }
     if (!stats) return COLBANDIT_OK;
 
     // statistics: the per-round survivor counts come back in one copy after the last kernel
-    (void)hipEventRecord(ev1, st);
     const size_t nh = (size_t)(R + 1) * n_queries;
     int32_t* hist = (int32_t*)malloc(sizeof(int32_t) * nh);
-    if (!hist) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); return COLBANDIT_ERR_HIP; }
+    if (!hist) { pt.destroy(); return COLBANDIT_ERR_HIP; }
     hipError_t ce = hipMemcpyAsync(hist, W.cnt_hist, sizeof(int32_t) * nh, hipMemcpyDeviceToHost, st);
     if (ce == hipSuccess) ce = hipStreamSynchronize(st);
-    float ms = 0.f;
-    if (ce == hipSuccess) (void)hipEventElapsedTime(&ms, ev0, ev1);
-    (void)hipEventDestroy(ev0);
-    (void)hipEventDestroy(ev1);
+    float ms = 0.f, phase_ms[PH_COUNT] = {0.f, 0.f, 0.f, 0.f};
+    if (ce == hipSuccess) pt.collect(phase_ms, ms);
+    pt.destroy();
     if (ce != hipSuccess) { free(hist); return COLBANDIT_ERR_HIP; }
     for (int q = 0; q < n_queries; ++q) {
         colbandit_stats& s = stats[q];
@@ -343,6 +404,10 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
         s.cells_rescore = (int64_t)T * count;
         s.cells_unique = s.cells_elim + (int64_t)(T - n) * count;
         s.ms_total = ms;
+        s.ms_first_reveal = phase_ms[PH_FIRST_REVEAL];
+        s.ms_later_reveals = phase_ms[PH_LATER_REVEAL];
+        s.ms_select_prune = phase_ms[PH_SELECT];
+        s.ms_rescore_topk = phase_ms[PH_RESCORE];
     }
     free(hist);
     return COLBANDIT_OK;

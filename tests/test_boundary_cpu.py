@@ -34,8 +34,8 @@ def test_struct_layouts_match_the_header(B):
     # survivors[MAX_ROUNDS + 2] and the limits the binding mirrors
     hdr = open(os.path.join(ROOT, "include", "colbandit.h")).read()
     assert int(re.search(r"#define COLBANDIT_MAX_ROUNDS (\d+)", hdr).group(1)) == B.MAX_ROUNDS
-    assert ctypes.sizeof(B.ColbanditStats) == 4 + 4 * (B.MAX_ROUNDS + 2) + 3 * 8 + 8 \
-        or ctypes.sizeof(B.ColbanditStats) % 8 == 0
+    assert ctypes.sizeof(B.ColbanditStats) == B.lib().colbandit_sizeof_stats()
+    assert ctypes.sizeof(B.ColbanditOpts) == B.lib().colbandit_sizeof_opts()
 
 
 def test_strerror_is_defined_for_every_code(B):
@@ -50,7 +50,7 @@ def _call_full(B, **kw):
     a.update(kw)
     return B.lib().colbandit_full_maxsim(a["Q"], a["nq"], a["T"], a["d"], a["dt"], a["docs"],
                                          a["off"], a["N"], a["total"], a["K"], a["scores"],
-                                         a["ids"], a["sc"], a["cells"], a["ws"], a["wsb"],
+                                         a["ids"], a["sc"], a["cells"], None, a["ws"], a["wsb"],
                                          a["stream"])
 
 
