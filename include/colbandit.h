@@ -81,6 +81,12 @@ typedef struct {
     int no_cell_cache;  /* nonzero: re-gather the documents in every round instead of
                            caching a small active set's cells at its first gather
                            (test aid; the decisions are the same either way)            */
+    int later_rounds;   /* reveal path of rounds >= 2 for bf16 inputs.  0: chosen on the
+                           device each round - one corpus-streaming pass shared by all
+                           queries when the active sets are so large that gathering
+                           every (query, document) pair would move more bytes, else the
+                           per-pair gather; 1: the streaming pass in every such round;
+                           2: always the gather.  The decisions are the same either way */
 } colbandit_opts;
 
 /*

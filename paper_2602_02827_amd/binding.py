@@ -31,7 +31,7 @@ class ColbanditOpts(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("a", ctypes.c_float), ("b", ctypes.c_float),
                 ("pi", ctypes.c_void_p), ("trace", ctypes.c_void_p),
                 ("trace_bytes", ctypes.c_size_t), ("force_gather", ctypes.c_int),
-                ("no_cell_cache", ctypes.c_int)]
+                ("no_cell_cache", ctypes.c_int), ("later_rounds", ctypes.c_int)]
 
 
 class ColbanditStats(ctypes.Structure):
@@ -213,10 +213,11 @@ def _parse_trace(buf: torch.Tensor, nq, T, B, N, queries=None) -> Trace:
 
 def colbandit_topk(Q, docs, offsets, K, alpha_ef=0.2, delta=0.01, M=5, seed=0, B=0, a=0.0, b=0.0,
                    pi=None, trace=False, force_gather=False, want_stats=True, workspace=None,
-                   out=None, no_cell_cache=False, trace_queries=None):
+                   out=None, no_cell_cache=False, trace_queries=None, later_rounds=0):
     """Col-Bandit top-K.  Returns dict(topk_ids, topk_scores, stats (list of dict) | None,
     trace (Trace) | None).  `pi`: optional int32 device tensor [nq,T]; `trace_queries`: keep
-    only these queries' columns of the trace (the device buffer still covers all of them)."""
+    only these queries' columns of the trace (the device buffer still covers all of them);
+    `later_rounds`: 0 auto, 1 corpus-streaming pass in every round >= 2, 2 always gather."""
     Q, nq, T, d, N, total = _shapes(Q, docs, offsets)
     dev = docs.device
     ws = workspace if workspace is not None else new_workspace(nq, T, d, N, total, dev)
@@ -227,7 +228,7 @@ def colbandit_topk(Q, docs, offsets, K, alpha_ef=0.2, delta=0.01, M=5, seed=0, B
         torch.empty((nq, K), dtype=torch.float32, device=dev)
     opts = ColbanditOpts(B=B, a=a, b=b, pi=None, trace=None, trace_bytes=0,
                          force_gather=1 if force_gather else 0,
-                         no_cell_cache=1 if no_cell_cache else 0)
+                         no_cell_cache=1 if no_cell_cache else 0, later_rounds=int(later_rounds))
     tbuf = None
     Beff = B if B > 0 else 4
     if pi is not None:

@@ -17,8 +17,8 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 constexpr int kChunkTokens = 4096;
 
 struct Layout {
-    size_t ctl, list0, list1, stat, rescored, scores, cnt_hist, tau_hist, pi, chunk_doc, flag,
-        cid, cstat, ccell, total;
+    size_t ctl, list0, list1, stat, stat2, pairs, rescored, scores, cnt_hist, tau_hist, pi,
+        chunk_doc, flag, cid, cstat, ccell, total;
     int cache_cap, TP;
 };
 
@@ -38,6 +38,8 @@ Layout make_layout(int nq, int T, int64_t N, int64_t total_tokens) {
     L.list0 = take(4 * qn);
     L.list1 = take(4 * qn);
     L.stat = take(8 * qn);
+    L.stat2 = take(8 * qn);
+    L.pairs = take(8 * (size_t)(COLBANDIT_MAX_ROUNDS + 4));
     L.rescored = take(4 * qn);
     L.scores = take(4 * qn);
     L.cnt_hist = take(4 * (size_t)(COLBANDIT_MAX_ROUNDS + 2) * nq);
@@ -64,6 +66,8 @@ Work carve(void* ws, const Layout& L) {
     W.list[0] = (int32_t*)(b + L.list0);
     W.list[1] = (int32_t*)(b + L.list1);
     W.stat = (float2*)(b + L.stat);
+    W.stat2 = (float2*)(b + L.stat2);
+    W.pairs = (unsigned long long*)(b + L.pairs);
     W.rescored = (float*)(b + L.rescored);
     W.scores = (float*)(b + L.scores);
     W.cnt_hist = (int32_t*)(b + L.cnt_hist);
@@ -137,6 +141,23 @@ struct PhaseTimer {
         n = 0;
     }
 };
+
+// Number of (query, document) pairs above which a later round is cheaper as one corpus pass
+// shared by all queries than as per-pair gathers.  Time model (seconds), with the rates these
+// kernels reach on an MI355X: a corpus pass costs the larger of streaming the tokens once
+// (~3.5 TB/s) and the matrix work of all query rows against them (~1.15 PFLOP/s); a gathered
+// pair streams its document once (~4.5 TB/s) and nothing is shared between queries.  A
+// gathered visit also caches the document's cells for the remaining rounds when the query fits
+// the cache, so the gather is preferred up to twice the cost of the pass.
+unsigned long long dense_pairs_threshold(const Problem& P, int G) {
+    const double row_bytes = 2.0 * P.d;
+    const double rows = (double)(((int64_t)P.nq * G + 15) / 16 * 16);
+    const double per_token = fmax(row_bytes / 3.5e12, 2.0 * rows * P.d / 1.15e15);
+    const double t_pass = (double)P.total * per_token;
+    const double t_pair = ((double)P.total / (double)P.N) * row_bytes / 4.5e12;
+    const double thr = 2.0 * t_pass / t_pair;
+    return thr >= 1.8e19 ? ~0ull - 1 : (unsigned long long)thr;
+}
 
 double rho_n(int n, int T) {
     // finite-population correction, Appendix A
@@ -294,6 +315,7 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
     void* trace = nullptr;
     size_t trace_bytes = 0;
     bool force_gather = false, no_cache = false;
+    int later_rounds = 0;
     if (opts) {
         if (opts->B < 0) return COLBANDIT_ERR_KNOB;
         if (opts->B > 0) kn.B = opts->B;
@@ -307,6 +329,8 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
         trace_bytes = opts->trace_bytes;
         force_gather = opts->force_gather != 0;
         no_cache = opts->no_cell_cache != 0;
+        if (opts->later_rounds < 0 || opts->later_rounds > 2) return COLBANDIT_ERR_KNOB;
+        later_rounds = opts->later_rounds;
     }
     if (kn.B > COLBANDIT_MAX_B) return COLBANDIT_ERR_UNSUPPORTED;
     const int R = (T + kn.B - 1) / kn.B;
@@ -354,12 +378,16 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
         rr.n = rr.lo + rr.nb;
         const double kap = colbandit_radius_prefactor(alpha_ef, delta, T, N, rr.n);
         rr.kappa = isinf(kap) ? 0.f : (float)kap;   // unused by the kernels when n <= 1
+        int G = 1;
+        while (G < rr.nb) G <<= 1;
+        rr.dense_thr = ~0ull;
         if (r == 1 && dense) {
-            int G = 1;
-            while (G < rr.nb) G <<= 1;
             e = launch_dense_reveal(P, W, kChunkTokens, n_chunks, rr, G, st);
         } else {
-            e = launch_gather_reveal(P, W, rr, st);
+            if (r >= 2 && dense && later_rounds != 2)
+                rr.dense_thr = later_rounds == 1 ? 0ull : dense_pairs_threshold(P, G);
+            e = launch_dense_reveal_later(P, W, kChunkTokens, n_chunks, rr, G, st);
+            if (e == hipSuccess) e = launch_gather_reveal(P, W, rr, st);
             if (e == hipSuccess && r >= 2) e = launch_gather_cells(P, W, rr, st);
         }
         pt.mark(r == 1 ? PH_FIRST_REVEAL : PH_LATER_REVEAL);

@@ -43,6 +43,11 @@ struct DenseArgs {
     const int32_t* pi;
     int lo, nb, G;
     float2* stat;
+    // a round >= 2: run only if dense_round(pairs_r, dense_thr); skip queries that are
+    // finished or read their cells from the cache
+    const unsigned long long* pairs_r;
+    unsigned long long dense_thr;
+    const QueryCtl* ctl;
 };
 
 template <int D, int NT, int TQ, bool REVEAL>
@@ -63,6 +68,9 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
     const int group = slot % A.n_groups;
     const int chunk = (slot / A.n_groups) * 8 + xcd;
     if (chunk >= A.n_chunks) return;
+    if constexpr (REVEAL) {
+        if (A.pairs_r && !dense_round(A.pairs_r, A.dense_thr)) return;
+    }
     int i0 = A.chunk_doc[chunk], i1 = A.chunk_doc[chunk + 1];
     i0 = i0 < 0 ? 0 : (i0 > (int)A.N ? (int)A.N : i0);
     i1 = i1 < i0 ? i0 : (i1 > (int)A.N ? (int)A.N : i1);
@@ -142,6 +150,24 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt) h[tt] = -__builtin_inff();
 
+    // reveal: which of this lane's result registers belong to a query that takes the batch
+    unsigned qmask = ~0u;
+    if constexpr (REVEAL) {
+        if (A.ctl) {
+            using P = Pack<NT>;
+            qmask = 0u;
+#pragma unroll
+            for (int j = 0; j < P::NW; ++j) {
+                const int x = (tile0 + P::tile_of_row(j, lane >> 4)) * 16 + col;
+                const int q = x / A.G;
+                if (q < A.nq) {
+                    const QueryCtl c = A.ctl[q];
+                    if (c.active && c.mode == 0) qmask |= 1u << j;
+                }
+            }
+        }
+    }
+
     // per-document epilogue: cross-lane maxima, then the row sum (score) or the batch
     // statistics (reveal), written by the lanes that own a query
     auto finalize = [&](int doc) {
@@ -156,7 +182,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
                 const int q = x / A.G, sl = x % A.G;
                 float sb, m2b;
                 batch_stats(w[j], sl, A.nb, A.G, sb, m2b);
-                if (sl == 0 && q < A.nq && P::row_is_primary(row))
+                if (sl == 0 && q < A.nq && P::row_is_primary(row) && ((qmask >> j) & 1u))
                     A.stat[(size_t)q * A.N + doc] = make_float2(sb, m2b);
             }
         } else {
@@ -365,6 +391,22 @@ hipError_t launch_dense_reveal(const Problem& P, const Work& W, int C, int n_chu
     A.lo = rr.lo;
     A.nb = rr.nb;
     A.G = G;
+    return P.d == 128 ? dense_reveal_d<128>(A, st) : dense_reveal_d<64>(A, st);
+}
+
+hipError_t launch_dense_reveal_later(const Problem& P, const Work& W, int C, int n_chunks,
+                                     const RevealRound& rr, int G, hipStream_t st) {
+    (void)C;
+    if (rr.dense_thr == ~0ull) return hipSuccess;
+    DenseArgs A{};
+    fill_dense(A, P, W, n_chunks);
+    A.lo = rr.lo;
+    A.nb = rr.nb;
+    A.G = G;
+    A.stat = W.stat2;
+    A.pairs_r = W.pairs + rr.r;
+    A.dense_thr = rr.dense_thr;
+    A.ctl = W.ctl;
     return P.d == 128 ? dense_reveal_d<128>(A, st) : dense_reveal_d<64>(A, st);
 }
 

@@ -31,6 +31,14 @@ struct QueryCtl {
     int pad0, pad1, pad2;
 };
 
+// Device-side choice of a later round's reveal path (uniform over the launch): true = the
+// corpus-streaming pass serves every active ids-mode query, false = per-pair gather.
+__device__ __forceinline__ bool dense_round(const unsigned long long* pairs_r,
+                                            unsigned long long thr) {
+    return pairs_r != nullptr && *pairs_r > thr;
+}
+
+
 // ---------------------------------------------------------------------------------
 // Operand fragments for the 16x16 MFMA family.  One fragment holds, for the lane's row
 // (lane & 15) of a 16-row operand block, the d/4 elements that the lane's k-group

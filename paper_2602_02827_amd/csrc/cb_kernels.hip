@@ -17,8 +17,10 @@ __device__ __forceinline__ uint64_t splitmix64_next(uint64_t& s) {
 
 __global__ void k_init(QueryCtl* ctl, int32_t* pi, const int32_t* user_pi, int32_t* cnt_hist,
                        float* tau_hist, int nq, int T, int R, int64_t N, int KM, uint64_t seed,
-                       int32_t* tr_count, float* tr_tau) {
+                       int32_t* tr_count, float* tr_tau, unsigned long long* pairs) {
     const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q == 0)
+        for (int r = 0; r <= R + 1; ++r) pairs[r] = 0ull;
     if (q >= nq) return;
     QueryCtl c;
     c.count = (int)N;
@@ -69,7 +71,8 @@ __global__ void k_fill_u8(uint8_t* p, size_t n, uint8_t v) {
 hipError_t launch_init(const Problem& P, const Work& W, const Knobs& kn, int R, uint64_t seed,
                        const int32_t* user_pi, const Trace& tr, hipStream_t st) {
     k_init<<<(P.nq + 63) / 64, 64, 0, st>>>(W.ctl, W.pi, user_pi, W.cnt_hist, W.tau_hist, P.nq,
-                                            P.T, R, P.N, kn.K + kn.M, seed, tr.count, tr.tau);
+                                            P.T, R, P.N, kn.K + kn.M, seed, tr.count, tr.tau,
+                                            W.pairs);
     if (tr.lcb) {
         const size_t n = (size_t)R * P.nq * P.N;
         const int g = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
@@ -116,6 +119,8 @@ struct GatherArgs {
     const int32_t* pi;
     int lo, nb, n_prev, G;
     float2* stat;
+    const unsigned long long* pairs_r;   // see dense_round(); nullptr: always gather
+    unsigned long long dense_thr;
     // cell cache
     int cache_cap, TP;
     int32_t* cid;
@@ -138,6 +143,7 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
 
     int count = (int)A.N;
     int32_t* list = nullptr;
+    if (MODE != GM_SCORE && dense_round(A.pairs_r, A.dense_thr)) return;   // the dense pass serves it
     if (A.ctl) {
         const QueryCtl c = A.ctl[q];
         if (c.mode != 0) return;
@@ -301,7 +307,9 @@ static hipError_t gather_by_d(const GatherArgs& A, int mode, const Problem& P, i
     return hipErrorInvalidValue;
 }
 
-static void fill_round(GatherArgs& A, const RevealRound& rr) {
+static void fill_round(GatherArgs& A, const Work& W, const RevealRound& rr) {
+    A.pairs_r = rr.dense_thr == ~0ull ? nullptr : W.pairs + rr.r;
+    A.dense_thr = rr.dense_thr;
     A.lo = rr.lo;
     A.nb = rr.nb;
     A.n_prev = rr.n_prev;
@@ -314,7 +322,7 @@ hipError_t launch_gather_reveal(const Problem& P, const Work& W, const RevealRou
     GatherArgs A{};
     fill_gather_common(A, P, W);
     A.ctl = W.ctl;
-    fill_round(A, rr);
+    fill_round(A, W, rr);
     return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, GM_REVEAL, P, P.N, st)
                            : gather_by_d<f32_tag>(A, GM_REVEAL, P, P.N, st);
 }
@@ -325,7 +333,7 @@ hipError_t launch_gather_cells(const Problem& P, const Work& W, const RevealRoun
     GatherArgs A{};
     fill_gather_common(A, P, W);
     A.ctl = W.ctl;
-    fill_round(A, rr);
+    fill_round(A, W, rr);
     return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, GM_CELLS, P, W.cache_cap, st)
                            : gather_by_d<f32_tag>(A, GM_CELLS, P, W.cache_cap, st);
 }
@@ -531,7 +539,10 @@ struct SelArgs {
     QueryCtl* ctl;
     int32_t* list0;
     int32_t* list1;
-    const float2* stat;
+    float2* stat;
+    const float2* stat2;
+    unsigned long long* pairs;           // [R+2]
+    unsigned long long dense_thr;        // ~0: this round cannot be a dense one
     int64_t N;
     int nq, T, K, KM;
     int r, n, n_prev, lo, nb, G;
@@ -569,7 +580,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
     int32_t* out = (out_sel ? A.list1 : A.list0) + (size_t)q * A.N;
     // entries are cache slots if the query was switched earlier (mode 1) or by this
     // round's cell-caching gather (same rule as in k_gather)
-    const bool slots = c.mode == 1 || (c.mode == 0 && !c.implicit && count <= A.cache_cap);
+    const bool dense = A.dense_thr != ~0ull && dense_round(A.pairs + A.r, A.dense_thr);
+    const bool slots = c.mode == 1 || (c.mode == 0 && !c.implicit && count <= A.cache_cap && !dense);
     const float2* stat = slots ? A.cstat + (size_t)q * A.cache_cap : A.stat + (size_t)q * A.N;
     const int32_t* cid = A.cid + (size_t)q * A.cache_cap;
     const int n = A.n, T = A.T;
@@ -588,6 +600,19 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
             float2 st = cst[e];
             merge_stats(st.x, st.y, A.n_prev, sb, m2b, A.nb);
             cst[e] = st;
+        }
+        __syncthreads();
+    }
+
+    if (dense && c.mode == 0 && in) {   // fold in the batch a dense pass left in stat2
+        float2* dst = A.stat + (size_t)q * A.N;
+        const float2* bat = A.stat2 + (size_t)q * A.N;
+        for (int idx = threadIdx.x; idx < count; idx += SEL_THREADS) {
+            const int e = in[idx];
+            float2 st = dst[e];
+            const float2 bb = bat[e];
+            merge_stats(st.x, st.y, A.n_prev, bb.x, bb.y, A.nb);
+            dst[e] = st;
         }
         __syncthreads();
     }
@@ -671,6 +696,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
         nc.mode = slots ? 1 : 0;
         nc.pad0 = nc.pad1 = nc.pad2 = 0;
         A.ctl[q] = nc;
+        // what the next round would have to gather: the active sets still held as ids
+        if (nc.active && nc.mode == 0) atomicAdd(A.pairs + A.r + 1, (unsigned long long)base);
         A.cnt_hist[A.r * A.nq + q] = base;
         A.tau_hist[(A.r - 1) * A.nq + q] = tau;
         if (A.tr_count) {
@@ -687,6 +714,9 @@ hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
     A.list0 = W.list[0];
     A.list1 = W.list[1];
     A.stat = W.stat;
+    A.stat2 = W.stat2;
+    A.pairs = W.pairs;
+    A.dense_thr = rr.dense_thr;
     A.N = P.N;
     A.nq = P.nq;
     A.T = P.T;

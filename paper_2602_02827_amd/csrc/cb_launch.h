@@ -22,6 +22,8 @@ struct Work {
     QueryCtl* ctl;        // [nq]
     int32_t* list[2];     // [nq][N] each: ids of the active set, ascending
     float2* stat;         // [nq][N] per (query, doc): revealed sum, centred sum of squares
+    float2* stat2;        // [nq][N] batch (sum, centred squares) of a later round's dense pass
+    unsigned long long* pairs;   // [R+2] pairs[r]: (query, doc) pairs round r would have to gather
     float* rescored;      // [nq][N] exact score of the k-th survivor
     float* scores;        // [nq][N] Full-MaxSim scores when the caller keeps none
     int32_t* cnt_hist;    // [(R+1)][nq]
@@ -50,6 +52,10 @@ struct RevealRound {
     int lo, nb;           // batch = pi[lo .. lo+nb)
     int n_prev, n;        // cells revealed before / after the round
     float kappa;          // radius per unit sigma_hat at n
+    // Rounds >= 2 pick their reveal path on the device: the corpus-streaming pass if
+    // pairs[r] > dense_thr, else the per-pair gather.  Every kernel of the round evaluates the
+    // same test.  ~0: always gather (also round 1, whose path the host fixes).
+    unsigned long long dense_thr;
 };
 
 struct Knobs {
@@ -82,6 +88,11 @@ hipError_t launch_dense_score(const Problem& P, const Work& W, int chunk_tokens,
                               float* out, float* cells, hipStream_t st);
 hipError_t launch_dense_reveal(const Problem& P, const Work& W, int chunk_tokens, int n_chunks,
                                const RevealRound& rr, int G, hipStream_t st);
+// The same pass for a round >= 2: runs only if the round's device-side test picks it, writes the
+// batch statistics of every (active ids-mode query, document) to stat2; k_select_prune merges
+// them into the running statistics of the documents still active.
+hipError_t launch_dense_reveal_later(const Problem& P, const Work& W, int chunk_tokens,
+                                     int n_chunks, const RevealRound& rr, int G, hipStream_t st);
 bool dense_supported(const Problem& P);
 
 hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,

@@ -1,0 +1,82 @@
+"""Knob sweeps of the two scoring paths on one synthetic configuration.
+
+    python -m paper_2602_02827_amd.sweep --config 4 --alpha 0.05 0.1 0.2 0.5 1.0 --K 1 5 10 50
+    python -m paper_2602_02827_amd.sweep --config 2 --K 100 500 1000 --M 0 5 10
+    python -m paper_2602_02827_amd.sweep --config 2 --nq 1            # single-query latency
+
+Prints one JSON line per (K, alpha_ef, M): batch latency of colbandit_full_maxsim and of
+colbandit_topk (events around `--reps` back-to-back asynchronous calls), coverage
+(unique revealed cells / (N*T), Sec. 3.1 Eq. (6)), Overlap@K against the exhaustive top-K, mean
+rounds and survivors entering the rescore.  The grid of alpha_ef x K follows the knob sweeps of
+the paper's evaluation (Sec. 5, implementation appendix "Default parameter setting").
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--nq", type=int, default=None)
+    ap.add_argument("--alpha", type=float, nargs="+", default=[0.2])
+    ap.add_argument("--K", type=int, nargs="+", default=[5])
+    ap.add_argument("--M", type=int, nargs="+", default=[5])
+    ap.add_argument("--B", type=int, default=4)
+    ap.add_argument("--reps", type=int, default=3)
+    args = ap.parse_args(argv)
+
+    import numpy as np
+    import torch
+    from . import binding as B, synth
+
+    assert torch.cuda.is_available(), "sweep needs a GPU"
+    B.lib()
+    w = synth.config(args.config, device="cuda", scale=args.scale, nq=args.nq)
+    nq, T, d, N, total = w.nq, w.T, w.d, w.N, w.total_tokens
+    ws = B.new_workspace(nq, T, d, N, total, "cuda")
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.reps
+
+    for K in args.K:
+        full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K, workspace=ws, want_scores=False)
+        ms_full = timed(lambda: B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K, workspace=ws,
+                                                        want_scores=False, out=full))
+        ids_full = full["topk_ids"].cpu().numpy()
+        for alpha in args.alpha:
+            for M in args.M:
+                run = lambda stats=False: B.colbandit_topk(w.Q, w.docs, w.offsets, K, alpha, w.delta, M,
+                                                           w.seed, B=args.B, workspace=ws, want_stats=stats)
+                ms_cb = timed(run)
+                res = run(True)
+                torch.cuda.synchronize()
+                ids = res["topk_ids"].cpu().numpy()
+                st = res["stats"]
+                overlap = float(np.mean([len(set(ids_full[q]) & set(ids[q])) / K for q in range(nq)]))
+                cov = sum(s["cells_unique"] for s in st) / (float(nq) * N * T)
+                print(json.dumps({
+                    "workload": w.name, "n_queries": nq, "N": N, "T": T, "d": d, "K": K, "alpha_ef": alpha,
+                    "M": M, "B": args.B, "full_ms": round(ms_full, 3), "colbandit_ms": round(ms_cb, 3),
+                    "speedup": round(ms_full / ms_cb, 2), "coverage": round(cov, 4),
+                    "overlap_at_k": round(overlap, 4),
+                    "mean_rounds": round(float(np.mean([s["rounds"] for s in st])), 2),
+                    "mean_rescored": round(float(np.mean([s["survivors"][s["rounds"]] for s in st])), 1),
+                    "ms_phases": {k[3:]: round(st[0][k], 3) for k in
+                                  ("ms_first_reveal", "ms_later_reveals", "ms_select_prune", "ms_rescore_topk")},
+                }), flush=True)
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -161,10 +161,10 @@ def _compare_rounds(oracle_mod, tr, q, Hq, K, M, Bsz, alpha, delta, pi, a=-1.0, 
 
 
 def _run_colbandit_case(B, oracle_mod, w, K, M, Bsz, alpha, delta=0.01, seed=0, a=0.0, b=0.0,
-                        force_gather=False, max_diverged=0.15):
+                        force_gather=False, max_diverged=0.15, later_rounds=0):
     full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=0, want_cells=True)
     res = B.colbandit_topk(w.Q, w.docs, w.offsets, K, alpha, delta, M, seed, B=Bsz, a=a, b=b,
-                           trace=True, force_gather=force_gather)
+                           trace=True, force_gather=force_gather, later_rounds=later_rounds)
     torch.cuda.synchronize()
     H = full["cells"].cpu().numpy().astype(np.float64)
     Sfull = full["scores"].cpu().numpy()
@@ -262,6 +262,46 @@ def test_cell_cache_and_regather_give_identical_runs(B, S, alpha, Bsz, T):
     torch.cuda.synchronize()
     assert max(s["rounds"] for s in r1["stats"]) >= 2
     _same_run(r1, r2)
+
+
+@pytest.mark.parametrize("alpha,Bsz,T,nq", [(1.0, 4, 32, 4), (0.5, 3, 24, 9), (1.0, 16, 100, 2), (0.2, 4, 32, 40)])
+def test_later_rounds_by_corpus_pass_or_by_gather_are_identical(B, S, oracle_mod, alpha, Bsz, T, nq):
+    """Rounds >= 2 revealed by the corpus-streaming pass (merged into the running statistics by
+    the prune kernel), by per-pair gathers, or by the device-side choice between them: the
+    same cells, the same merge, so every bound, threshold, survivor and output bit agrees."""
+    rng = np.random.default_rng(100 + T)
+    w = _custom(S, rng.integers(1, 90, 3000).tolist(), nq, T, 128, "bf16", 17)
+    runs = [B.colbandit_topk(w.Q, w.docs, w.offsets, 5, alpha, 0.01, 5, 4, B=Bsz, trace=True,
+                             later_rounds=m) for m in (2, 1, 0)]
+    torch.cuda.synchronize()
+    assert max(s["rounds"] for s in runs[0]["stats"]) >= 3
+    _same_run(runs[0], runs[1])
+    _same_run(runs[0], runs[2])
+    # the streaming pass also under the cache-free mode, and against the oracle
+    r3 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, alpha, 0.01, 5, 4, B=Bsz, trace=True,
+                          later_rounds=1, no_cell_cache=True)
+    torch.cuda.synchronize()
+    _same_run(runs[0], r3)
+    _run_colbandit_case(B, oracle_mod, w, 5, 5, Bsz, alpha, seed=4, later_rounds=1)
+
+
+def test_device_side_choice_takes_the_corpus_pass_for_large_active_sets(B, S):
+    """A conservative radius on a topic corpus keeps thousands of documents per query alive:
+    the automatic mode must then not fall behind the exhaustive path by gathering them all."""
+    w = S.config(4, device="cuda", scale=0.2, nq=64)                 # N=20,000, 64 queries
+    ws = B.new_workspace(w.nq, w.T, w.d, w.N, w.total_tokens, "cuda")
+    res = {}
+    for m in (0, 2):
+        r = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 1.0, 0.01, 5, w.seed, workspace=ws,
+                             later_rounds=m)
+        res[m] = r
+    torch.cuda.synchronize()
+    assert torch.equal(res[0]["topk_ids"], res[2]["topk_ids"])
+    assert torch.equal(res[0]["topk_scores"], res[2]["topk_scores"])
+    c = lambda st: {k: v for k, v in st.items() if not k.startswith("ms_")}
+    assert [c(a) for a in res[0]["stats"]] == [c(b) for b in res[2]["stats"]]
+    print("later reveals: auto %.3f ms, gather %.3f ms" %
+          (res[0]["stats"][0]["ms_later_reveals"], res[2]["stats"][0]["ms_later_reveals"]))
 
 
 def test_active_sets_larger_than_the_cell_cache(B, S, oracle_mod):
