@@ -88,7 +88,8 @@ int check_shapes(const void* Q, int nq, int T, int d, int dt, const void* docs,
     if (!Q || !docs || !off) return COLBANDIT_ERR_NULL;
     if (nq < 1 || T < 1 || d < 1 || N < 1 || total < N) return COLBANDIT_ERR_SHAPE;
     if (dt != COLBANDIT_F32 && dt != COLBANDIT_BF16) return COLBANDIT_ERR_SHAPE;
-    if (N > 0x7fffffff - 1024 || nq > 65535) return COLBANDIT_ERR_UNSUPPORTED;
+    // the selection kernels index a list a few chunks (of up to 16,384 entries) past its end
+    if (N > 0x7fffffff - (1 << 17) || nq > 65535) return COLBANDIT_ERR_UNSUPPORTED;
     if (d != 64 && d != 128) return COLBANDIT_ERR_UNSUPPORTED;
     if (T > (dt == COLBANDIT_BF16 ? COLBANDIT_MAX_T : 64)) return COLBANDIT_ERR_UNSUPPORTED;
     if (((uintptr_t)Q & 15) || ((uintptr_t)docs & 15) || ((uintptr_t)off & 7))

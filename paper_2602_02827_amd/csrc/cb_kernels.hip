@@ -1,5 +1,7 @@
 // Gather-reveal / rescore kernel, bound-driven selection and pruning, top-K, and the
 // small control kernels.  gfx950 only.
+#include <type_traits>
+
 #include "cb_launch.h"
 
 namespace cb {
@@ -398,8 +400,18 @@ constexpr int SEL_THREADS = 1024;
 constexpr int SEL_WAVES = SEL_THREADS / 64;
 constexpr int SEL_ITEMS = 4;                       // consecutive entries per thread per chunk
 constexpr int SEL_CHUNK = SEL_THREADS * SEL_ITEMS;
-constexpr int SEL_SAMPLE = 16384;                 // strided sample behind the pre-filter
+constexpr int SEL_ITEMS_WIDE = 8;                  // the same for the one streaming pass over a long list
+constexpr int SEL_SAMPLE = 16384;                 // sample behind the pre-filter
 constexpr int SEL_PREFILTER_MIN = 8 * SEL_SAMPLE;  // lists longer than this are pre-filtered
+constexpr int SEL_RUN = 16;                        // the sample is taken in runs of adjacent entries
+
+// Position of sample j in a list of `count` > SEL_PREFILTER_MIN entries: SEL_SAMPLE / SEL_RUN
+// evenly spaced runs of SEL_RUN adjacent entries (whole cache lines instead of one entry per
+// line; any subset gives a valid lower threshold).
+__device__ __forceinline__ int sample_pos(int j, int count) {
+    const int run_stride = count / (SEL_SAMPLE / SEL_RUN);
+    return (j / SEL_RUN) * run_stride + (j % SEL_RUN);
+}
 
 // Exclusive scan of v over the block in thread order; returns the thread's offset and the
 // block total.  wtot: LDS int[SEL_WAVES].  Two barriers.
@@ -628,23 +640,41 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
     // Stable compaction of {entry of l[0..cnt) : UCB >= thr} into outl (outl may be l itself:
     // a chunk is read completely before anything is written, and writes stay below the
     // next chunk).  The trace takes every dropped entry, and the kept ones if trace_kept.
-    auto filter = [&](const int32_t* l, int cnt, int32_t* outl, float thr, bool trace_kept) -> int {
+    auto filter = [&](auto items_c, const int32_t* l, int cnt, int32_t* outl, float thr,
+                      bool trace_kept) -> int {
+        constexpr int ITEMS = decltype(items_c)::value;      // entries per thread per chunk
+        constexpr int CHUNK = SEL_THREADS * ITEMS;
         int base = 0;
-        for (int start = 0; start < cnt; start += SEL_CHUNK) {
-            const int i0 = start + threadIdx.x * SEL_ITEMS;     // SEL_ITEMS consecutive entries
-            int e[SEL_ITEMS];
-            float2 st[SEL_ITEMS];
+        // software pipeline over chunks: the entries are fetched two chunks ahead and their
+        // statistics one chunk ahead, so the loads of the next chunk are in flight across
+        // this chunk's scan and its barriers
+        const int t0 = threadIdx.x * ITEMS;                 // ITEMS consecutive entries
+        auto load_e = [&](int start, int (&e)[ITEMS]) {
 #pragma unroll
-            for (int u = 0; u < SEL_ITEMS; ++u) {
-                const int idx = i0 + u;
+            for (int u = 0; u < ITEMS; ++u) {
+                const int idx = start + t0 + u;
                 e[u] = idx < cnt ? (l ? l[idx] : idx) : 0;
             }
+        };
+        auto load_s = [&](int start, const int (&e)[ITEMS], float2 (&st)[ITEMS]) {
 #pragma unroll
-            for (int u = 0; u < SEL_ITEMS; ++u)
-                st[u] = (i0 + u < cnt) ? stat[e[u]] : make_float2(0.f, 0.f);
+            for (int u = 0; u < ITEMS; ++u)
+                st[u] = (start + t0 + u < cnt) ? stat[e[u]] : make_float2(0.f, 0.f);
+        };
+        int e[ITEMS], e_next[ITEMS];
+        float2 st[ITEMS];
+        load_e(0, e);
+        load_s(0, e, st);
+        load_e(CHUNK, e_next);
+        for (int start = 0; start < cnt; start += CHUNK) {
+            const int i0 = start + t0;
+            int e_next2[ITEMS];
+            float2 st_next[ITEMS];
+            load_s(start + CHUNK, e_next, st_next);
+            load_e(start + 2 * CHUNK, e_next2);
             unsigned keep = 0;
 #pragma unroll
-            for (int u = 0; u < SEL_ITEMS; ++u) {
+            for (int u = 0; u < ITEMS; ++u) {
                 if (i0 + u < cnt) {
                     float lcb, ucb;
                     interval(st[u].x, st[u].y, n, T, kappa, a, b, lcb, ucb);
@@ -658,12 +688,20 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
                     }
                 }
             }
-            int total;
-            int pos = base + block_excl_scan(__popc(keep), wtot, total);
+            if (__syncthreads_or(keep != 0)) {          // a pre-filter keeps nothing of most chunks
+                int total;
+                int pos = base + block_excl_scan(__popc(keep), wtot, total);
 #pragma unroll
-            for (int u = 0; u < SEL_ITEMS; ++u)
-                if (keep & (1u << u)) outl[pos++] = e[u];
-            base += total;
+                for (int u = 0; u < ITEMS; ++u)
+                    if (keep & (1u << u)) outl[pos++] = e[u];
+                base += total;
+            }
+#pragma unroll
+            for (int u = 0; u < ITEMS; ++u) {
+                e[u] = e_next[u];
+                st[u] = st_next[u];
+                e_next[u] = e_next2[u];
+            }
         }
         return base;
     };
@@ -676,16 +714,16 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
     const int32_t* sel_in = in;
     int sel_count = count;
     if (count > SEL_PREFILTER_MIN) {
-        const int stride = count / SEL_SAMPLE;
-        auto key_s = [&](int j) -> uint32_t { return key_of(in, j * stride); };
+        auto key_s = [&](int j) -> uint32_t { return key_of(in, sample_pos(j, count)); };
         const float tau_lo = key_float(block_kth_largest(SEL_SAMPLE, A.K, key_s, hist, pick));
-        sel_count = filter(in, count, out, tau_lo, false);
+        // the streaming pass: wide chunks keep enough loads in flight for one workgroup
+        sel_count = filter(std::integral_constant<int, SEL_ITEMS_WIDE>{}, in, count, out, tau_lo, false);
         sel_in = out;
     }
     auto key_sel = [&](int idx) -> uint32_t { return key_of(sel_in, idx); };
     const uint32_t tkey = block_kth_largest(sel_count, A.K, key_sel, hist, pick);
     const float tau = key_float(tkey);
-    const int base = filter(sel_in, sel_count, out, tau, true);
+    const int base = filter(std::integral_constant<int, SEL_ITEMS>{}, sel_in, sel_count, out, tau, true);
 
     if (threadIdx.x == 0) {
         QueryCtl nc;
@@ -796,21 +834,30 @@ __global__ __launch_bounds__(SEL_THREADS) void k_topk(TopkArgs A) {
         int ncand = count;
         if (count > SEL_PREFILTER_MIN) {
             int32_t* tmp = scratch;
-            const int stride = count / SEL_SAMPLE;
-            auto key_s = [&](int j) -> uint32_t { return float_key(vals[j * stride]); };
+            auto key_s = [&](int j) -> uint32_t { return float_key(vals[sample_pos(j, count)]); };
             const uint32_t lo = block_kth_largest(SEL_SAMPLE, Kq, key_s, hist, pick);
             int base = 0;
-            for (int start = 0; start < count; start += SEL_CHUNK) {
-                const int i0 = start + threadIdx.x * SEL_ITEMS;
+            const int t0 = threadIdx.x * SEL_ITEMS_WIDE;
+            float v[SEL_ITEMS_WIDE];                       // the next chunk's values are fetched
+#pragma unroll                                        // before this chunk's barriers
+            for (int u = 0; u < SEL_ITEMS_WIDE; ++u) v[u] = t0 + u < count ? vals[t0 + u] : 0.f;
+            for (int start = 0; start < count; start += (SEL_THREADS * SEL_ITEMS_WIDE)) {
+                const int i0 = start + t0;
+                float v_next[SEL_ITEMS_WIDE];
+#pragma unroll
+                for (int u = 0; u < SEL_ITEMS_WIDE; ++u)
+                    v_next[u] = i0 + (SEL_THREADS * SEL_ITEMS_WIDE) + u < count ? vals[i0 + (SEL_THREADS * SEL_ITEMS_WIDE) + u] : 0.f;
                 unsigned keep = 0;
 #pragma unroll
-                for (int u = 0; u < SEL_ITEMS; ++u)
-                    if (i0 + u < count && float_key(vals[i0 + u]) >= lo) keep |= 1u << u;
+                for (int u = 0; u < SEL_ITEMS_WIDE; ++u)
+                    if (i0 + u < count && float_key(v[u]) >= lo) keep |= 1u << u;
+#pragma unroll
+                for (int u = 0; u < SEL_ITEMS_WIDE; ++u) v[u] = v_next[u];
                 if (__syncthreads_or(keep != 0)) {
                     int total;
                     int pos = base + block_excl_scan(__popc(keep), wtot, total);
 #pragma unroll
-                    for (int u = 0; u < SEL_ITEMS; ++u)
+                    for (int u = 0; u < SEL_ITEMS_WIDE; ++u)
                         if (keep & (1u << u)) tmp[pos++] = i0 + u;
                     base += total;
                 }
