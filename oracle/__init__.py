@@ -184,6 +184,75 @@ def colbandit_from_H(H, K, M, B, alpha, delta, pi, a=-1.0, b=1.0, trace=True):
                            None if alive is None else alive[:rc].astype(bool))
 
 
+def colbandit_coarse(H_coarse, H_exact, K, M, B, alpha, delta, pi, a=-1.0, b=1.0, trace=True):
+    """Algorithm 1 deciding on coarse cells and rescoring the survivors from exact ones
+    (implementation appendix, cache-separated quantized layout)."""
+    Hc = np.ascontiguousarray(H_coarse, dtype=np.float64)
+    He = np.ascontiguousarray(H_exact, dtype=np.float64)
+    assert Hc.shape == He.shape
+    N, T = Hc.shape
+    pi = np.ascontiguousarray(pi, dtype=np.int32)
+    Rmax = (T + B - 1) // B
+    out_ids = np.full(K, -1, dtype=np.int64)
+    out_s = np.full(K, np.nan, dtype=np.float64)
+    final_ids = np.empty(N, dtype=np.int64)
+    n_final = ctypes.c_int64(0)
+    counts = np.full(Rmax + 1, -1, dtype=np.int64)
+    tau = np.full(Rmax, np.nan, dtype=np.float64)
+    cells = np.zeros(3, dtype=np.int64)
+    lcb = np.empty((Rmax, N), dtype=np.float64) if trace else None
+    ucb = np.empty((Rmax, N), dtype=np.float64) if trace else None
+    alive = np.empty((Rmax, N), dtype=np.uint8) if trace else None
+    rc = _check(_L().oracle_colbandit_coarse(
+        _p(Hc, ctypes.c_double), _p(He, ctypes.c_double), ctypes.c_int64(N), T, K, M, B,
+        ctypes.c_double(alpha), ctypes.c_double(delta), ctypes.c_double(a), ctypes.c_double(b),
+        _p(pi, ctypes.c_int32), _p(out_ids, ctypes.c_int64), _p(out_s, ctypes.c_double),
+        _p(final_ids, ctypes.c_int64), ctypes.byref(n_final), _p(counts, ctypes.c_int64),
+        _p(tau, ctypes.c_double), _p(lcb, ctypes.c_double), _p(ucb, ctypes.c_double),
+        _p(alive, ctypes.c_uint8), _p(cells, ctypes.c_int64)), "colbandit_coarse")
+    return ColBanditResult(out_ids, out_s, final_ids[: n_final.value].copy(), rc,
+                           counts[: rc + 1].copy(), tau[:rc].copy(),
+                           int(cells[0]), int(cells[1]), int(cells[2]),
+                           None if lcb is None else lcb[:rc],
+                           None if ucb is None else ucb[:rc],
+                           None if alive is None else alive[:rc].astype(bool))
+
+
+def abs_percentile(x, permille=999) -> float:
+    """Nearest-rank percentile (permille/1000) of |x| over all entries of x."""
+    x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    out = ctypes.c_float(0.0)
+    _check(_L().oracle_abs_percentile(_p(x, ctypes.c_float), ctypes.c_int64(x.size), int(permille),
+                                      ctypes.byref(out)), "abs_percentile")
+    return float(out.value)
+
+
+def quantize_i8(x, clip) -> np.ndarray:
+    """int8 codes of x after clipping at +-clip (same shape as x)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.int8)
+    _check(_L().oracle_quantize_i8(_p(x, ctypes.c_float), ctypes.c_int64(x.size), ctypes.c_float(clip),
+                                   _p(out, ctypes.c_int8)), "quantize_i8")
+    return out
+
+
+def maxsim_cells_i8(Q8, sq, D8, sd, offsets):
+    """(H [N,T] float64 decoded coarse cells, Hint [N,T] int32 integer maxima)."""
+    Q8 = np.ascontiguousarray(Q8, dtype=np.int8)
+    D8 = np.ascontiguousarray(D8, dtype=np.int8)
+    offsets = _i64(offsets)
+    T, d = Q8.shape
+    N = offsets.shape[0] - 1
+    H = np.empty((N, T), dtype=np.float64)
+    Hint = np.empty((N, T), dtype=np.int32)
+    _check(_L().oracle_maxsim_cells_i8(_p(Q8, ctypes.c_int8), ctypes.c_float(sq), T, d,
+                                       _p(D8, ctypes.c_int8), ctypes.c_float(sd),
+                                       _p(offsets, ctypes.c_int64), ctypes.c_int64(N),
+                                       _p(H, ctypes.c_double), _p(Hint, ctypes.c_int32)),
+           "maxsim_cells_i8")
+    return H, Hint
+
+
 def colbandit_lazy(Q, E, offsets, K, M, B, alpha, delta, pi, a=-1.0, b=1.0):
     """Algorithm 1 computing each revealed cell from the embeddings."""
     Q, E, offsets = _f32(Q), _f32(E), _i64(offsets)

@@ -253,6 +253,9 @@ typedef struct {
     const float *E;
     const int64_t *off;
     int T, d;
+    /* exact cells for the rescore when H holds coarse (quantised) estimates;
+       NULL: the rescore reads the same source as the reveals */
+    const double *H_exact;
 } cell_source_t;
 
 static double reveal(const cell_source_t *src, int64_t i, int t)
@@ -260,6 +263,13 @@ static double reveal(const cell_source_t *src, int64_t i, int t)
     if (src->H)
         return src->H[(size_t)i * src->T + t];
     return oracle_cell(src->Q, t, src->d, src->E, src->off, i);
+}
+
+static double exact_cell(const cell_source_t *src, int64_t i, int t)
+{
+    if (src->H_exact)
+        return src->H_exact[(size_t)i * src->T + t];
+    return reveal(src, i, t);
 }
 
 static int cmp_desc(const void *pa, const void *pb)
@@ -369,7 +379,7 @@ static int colbandit_core(const cell_source_t *src, int64_t N, int K, int M, int
         int64_t i = A[x];
         double s = 0.0;
         for (int t = 0; t < T; ++t)
-            s += reveal(src, i, t);
+            s += exact_cell(src, i, t);
         S[x] = s;
     }
     int rc = oracle_topk(S, A, nA, K, out_ids, out_scores);
@@ -398,9 +408,121 @@ int oracle_colbandit_from_H(const double *H, int64_t N, int T, int K, int M, int
 {
     if (!H || T < 1)
         return ORACLE_ERR_ARG;
-    cell_source_t src = {H, NULL, NULL, NULL, T, 0};
+    cell_source_t src = {H, NULL, NULL, NULL, T, 0, NULL};
     return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, out_ids, out_scores,
                           final_ids, n_final, counts, tau, tr_lcb, tr_ucb, tr_alive, cells);
+}
+
+/*
+ * Col-Bandit whose elimination loop sees coarse cells H_coarse while the survivors are
+ * rescored from the exact cells H_exact (implementation appendix, "Cache-separated
+ * quantized layout": decisions on the int8 estimates, exact rescore of the survivors).
+ */
+int oracle_colbandit_coarse(const double *H_coarse, const double *H_exact, int64_t N, int T,
+                            int K, int M, int B, double alpha, double delta, double a,
+                            double b, const int32_t *pi,
+                            int64_t *out_ids, double *out_scores,
+                            int64_t *final_ids, int64_t *n_final,
+                            int64_t *counts, double *tau,
+                            double *tr_lcb, double *tr_ucb, uint8_t *tr_alive,
+                            int64_t *cells)
+{
+    if (!H_coarse || !H_exact || T < 1)
+        return ORACLE_ERR_ARG;
+    cell_source_t src = {H_coarse, NULL, NULL, NULL, T, 0, H_exact};
+    return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, out_ids, out_scores,
+                          final_ids, n_final, counts, tau, tr_lcb, tr_ucb, tr_alive, cells);
+}
+
+/* ------------------------------------------------------------------ */
+/* int8 coarse pass (implementation appendix, "Cache-separated          */
+/* quantized layout": clip to the 99.9th percentile of the absolute     */
+/* values, then linear quantisation to int8)                            */
+/* ------------------------------------------------------------------ */
+
+static int cmp_float_asc(const void *pa, const void *pb)
+{
+    float a = *(const float *)pa, b = *(const float *)pb;
+    return (a < b) ? -1 : (a > b) ? 1 : 0;
+}
+
+/*
+ * Clip value: the nearest-rank percentile of |x| -- the smallest v such that at
+ * least permille/1000 of the n values satisfy |x| <= v, i.e. the element of rank
+ * ceil(n * permille / 1000) (1-based) of the ascending sort.  Readings: the
+ * paper does not say which percentile definition or which population; here the
+ * population is whatever array is handed in (the whole corpus matrix, or one
+ * query's T x d matrix) and the definition is nearest-rank, which needs no
+ * interpolation and is therefore reproducible bit for bit.
+ */
+int oracle_abs_percentile(const float *x, int64_t n, int permille, float *clip)
+{
+    if (!x || !clip || n < 1 || permille < 1 || permille > 1000)
+        return ORACLE_ERR_ARG;
+    float *v = (float *)malloc(sizeof(float) * (size_t)n);
+    if (!v)
+        return ORACLE_ERR_NOMEM;
+    for (int64_t i = 0; i < n; ++i)
+        v[i] = fabsf(x[i]);
+    qsort(v, (size_t)n, sizeof(float), cmp_float_asc);
+    /* ceil(n * permille / 1000) in integers; n * 1000 fits int64 for any array in memory */
+    int64_t rank = (n * (int64_t)permille + 999) / 1000;
+    if (rank < 1) rank = 1;
+    *clip = v[rank - 1];
+    free(v);
+    return ORACLE_OK;
+}
+
+/*
+ * Linear quantisation to int8 after clipping at +-clip: code = round-half-even(x * (127/clip))
+ * saturated to [-127, 127]; the decoded value is code * (clip/127).  A floating-point value
+ * decides an integer here, so the arithmetic is fixed: 127/clip and the product are single
+ * precision operations (the precision of the kernels), rounding is to nearest even.
+ * clip == 0 (an all-zero array) gives all-zero codes.
+ */
+int oracle_quantize_i8(const float *x, int64_t n, float clip, int8_t *out)
+{
+    if (!x || !out || n < 0 || !(clip >= 0.0f))
+        return ORACLE_ERR_ARG;
+    volatile float inv = clip > 0.0f ? 127.0f / clip : 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float y = x[i] * inv;       /* one single-precision rounding */
+        float r = rintf(y);                  /* default mode: to nearest, ties to even */
+        if (r > 127.0f) r = 127.0f;
+        if (r < -127.0f) r = -127.0f;
+        out[i] = (int8_t)r;
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Coarse MaxSim matrix from int8 codes: H[i][t] = sq * sd * max_j sum_k Q8[t][k] * D8[j][k],
+ * the integer dot products exact, sq and sd the two decode scales (clip/127).
+ * Also returns the integer maxima if Hint is non-NULL.
+ */
+int oracle_maxsim_cells_i8(const int8_t *Q8, float sq, int T, int d, const int8_t *D8, float sd,
+                           const int64_t *off, int64_t N, double *H, int32_t *Hint)
+{
+    if (!Q8 || !D8 || !off || !H || T < 1 || d < 1 || N < 0)
+        return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < N; ++i) {
+        if (off[i + 1] <= off[i])
+            return ORACLE_ERR_EMPTY_DOC;
+        for (int t = 0; t < T; ++t) {
+            int64_t best = 0;
+            for (int64_t j = off[i]; j < off[i + 1]; ++j) {
+                int64_t acc = 0;
+                for (int k = 0; k < d; ++k)
+                    acc += (int64_t)Q8[(size_t)t * d + k] * (int64_t)D8[(size_t)j * d + k];
+                if (j == off[i] || acc > best)
+                    best = acc;
+            }
+            H[(size_t)i * T + t] = (double)best * (double)sq * (double)sd;
+            if (Hint)
+                Hint[(size_t)i * T + t] = (int32_t)best;
+        }
+    }
+    return ORACLE_OK;
 }
 
 /* Col-Bandit that computes each revealed cell from the embeddings. */
@@ -417,7 +539,7 @@ int oracle_colbandit_lazy(const float *Q, int T, int d, const float *E,
     for (int64_t i = 0; i < N; ++i)
         if (off[i + 1] <= off[i])
             return ORACLE_ERR_EMPTY_DOC;
-    cell_source_t src = {NULL, Q, E, off, T, d};
+    cell_source_t src = {NULL, Q, E, off, T, d, NULL};
     return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, out_ids, out_scores,
                           final_ids, n_final, counts, tau, NULL, NULL, NULL, cells);
 }

@@ -404,3 +404,118 @@ def test_pac_corner_over_all_permutations(oracle_mod):
     # theorem is about, and it is checked above.
     print(f"alpha_ef=1: top-K set wrong in {bad_set}/{total} orders, "
           f"some live interval missed its row sum in {bad_interval}/{total} orders")
+
+
+# ------------------------------------------------------------------ int8 coarse pass
+# (implementation appendix, "Cache-separated quantized layout": clip at the 99.9th percentile of
+# the absolute values, linear int8 codes, decisions on the coarse cells, exact rescore)
+
+def test_abs_percentile_is_the_nearest_rank_statistic(oracle_mod):
+    rng = np.random.default_rng(5)
+    for n in (1, 7, 1000, 4096, 12345):
+        x = rng.standard_normal(n).astype(np.float32)
+        for permille in (500, 900, 999, 1000):
+            got = oracle_mod.abs_percentile(x, permille)
+            # library routine with the same definition (inverse of the empirical CDF)
+            want = np.percentile(np.abs(x), permille / 10.0, method="inverted_cdf")
+            assert got == np.float32(want), (n, permille)
+            # the defining property, by counting
+            frac = np.mean(np.abs(x) <= got)
+            assert frac * 1000 >= permille - 1e-9
+            below = np.abs(x)[np.abs(x) < got]
+            assert len(below) * 1000 < permille * n or len(below) == 0
+    # worked example: ranks of 1..1000 -> the 999th value; T x d = 4096 -> rank 4092
+    assert oracle_mod.abs_percentile(-np.arange(1, 1001, dtype=np.float32)) == 999.0
+    assert oracle_mod.abs_percentile(np.arange(1, 4097, dtype=np.float32)) == 4092.0
+
+
+def test_quantize_i8_grid_saturation_and_error_bound(oracle_mod):
+    rng = np.random.default_rng(6)
+    clip = 0.37
+    s = np.float32(clip) / np.float32(127.0)
+    x = (rng.standard_normal(5000) * 0.15).astype(np.float32)
+    q = oracle_mod.quantize_i8(x, clip)
+    assert q.dtype == np.int8 and q.min() >= -127 and q.max() <= 127
+    inside = np.abs(x) <= clip
+    # inside the clip range the decoded value is within half a step (plus fp32 slack)
+    assert np.all(np.abs(q[inside].astype(np.float64) * s - x[inside]) <= 0.5 * s * (1 + 1e-5))
+    # outside it saturates with the sign of x
+    assert np.all(q[~inside] == np.sign(x[~inside]) * 127)
+    # odd symmetry, zero, exact grid points and ties to even
+    np.testing.assert_array_equal(oracle_mod.quantize_i8(-x, clip), -q)
+    grid = np.arange(-127, 128)
+    np.testing.assert_array_equal(oracle_mod.quantize_i8((grid * 1.0).astype(np.float32), 127.0), grid)
+    np.testing.assert_array_equal(oracle_mod.quantize_i8(np.array([0.5, 1.5, 2.5, -0.5, -1.5], np.float32), 127.0),
+                                  [0, 2, 2, 0, -2])
+    np.testing.assert_array_equal(oracle_mod.quantize_i8(np.array([3.0, -9.0, 0.0], np.float32), 0.0), [0, 0, 0])
+    # monotone
+    xs = np.sort(x)
+    assert np.all(np.diff(oracle_mod.quantize_i8(xs, clip).astype(np.int32)) >= 0)
+
+
+def test_coarse_cells_brute_force_and_exact_on_grid_inputs(oracle_mod):
+    rng = np.random.default_rng(7)
+    T, d, lens = 5, 16, [1, 3, 2, 4]
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    Q8 = rng.integers(-127, 128, (T, d)).astype(np.int8)
+    D8 = rng.integers(-127, 128, (int(off[-1]), d)).astype(np.int8)
+    sq, sd = np.float32(0.011), np.float32(0.007)
+    H, Hint = oracle_mod.maxsim_cells_i8(Q8, sq, D8, sd, off)
+    for i in range(len(lens)):
+        for t in range(T):
+            dots = [sum(int(Q8[t, k]) * int(D8[j, k]) for k in range(d)) for j in range(off[i], off[i + 1])]
+            assert Hint[i, t] == max(dots)
+            assert H[i, t] == pytest.approx(max(dots) * float(sq) * float(sd), rel=1e-15)
+    # inputs that already sit on the code grid: coarse cells equal the exact MaxSim cells
+    Qf = Q8.astype(np.float32) * sq
+    Df = D8.astype(np.float32) * sd
+    np.testing.assert_allclose(H, oracle_mod.maxsim_cells(Qf, Df, off), rtol=1e-6, atol=1e-9)
+    # ... and quantising them with clip = 127 * scale reproduces the codes
+    np.testing.assert_array_equal(oracle_mod.quantize_i8(Df, float(np.float32(127.0) * sd)), D8)
+
+
+def test_coarse_elimination_with_exact_rescore(oracle_mod):
+    """Decisions follow the coarse matrix, scores come from the exact one."""
+    rng = np.random.default_rng(8)
+    N, T, K, M, B = 300, 16, 3, 2, 4
+    H = rng.uniform(-0.2, 0.9, (N, T))
+    Hc = H + rng.normal(0, 0.01, (N, T))
+    pi = oracle_mod.permutation(1, 0, T)
+    r_c = oracle_mod.colbandit_coarse(Hc, H, K, M, B, 0.3, 0.01, pi)
+    r_ref = oracle_mod.colbandit_from_H(Hc, K, M, B, 0.3, 0.01, pi)
+    # same rounds, thresholds and survivors as the loop run on the coarse matrix alone
+    assert r_c.rounds == r_ref.rounds
+    np.testing.assert_array_equal(r_c.counts, r_ref.counts)
+    np.testing.assert_array_equal(r_c.tau, r_ref.tau)
+    np.testing.assert_array_equal(r_c.final_ids, r_ref.final_ids)
+    # scores of the output are the exact row sums, ordered by them
+    S = H.sum(axis=1)
+    fin = r_c.final_ids
+    order = fin[np.lexsort((fin, -S[fin]))][:K]
+    np.testing.assert_array_equal(r_c.topk_ids, order)
+    np.testing.assert_allclose(r_c.topk_scores, S[order], rtol=1e-14)
+    # identical matrices: the plain algorithm
+    r_same = oracle_mod.colbandit_coarse(H, H, K, M, B, 0.3, 0.01, pi)
+    r_plain = oracle_mod.colbandit_from_H(H, K, M, B, 0.3, 0.01, pi)
+    np.testing.assert_array_equal(r_same.topk_ids, r_plain.topk_ids)
+    np.testing.assert_array_equal(r_same.topk_scores, r_plain.topk_scores)
+
+
+def test_quantisation_error_of_coarse_cells_is_bounded(oracle_mod):
+    """|coarse - exact| <= sum_k (|q| e_d + |e| e_q + e_q e_d) with half-step errors, for values
+    inside the clip range (clip at the maximum so that nothing saturates)."""
+    rng = np.random.default_rng(9)
+    T, d = 8, 32
+    lens = rng.integers(1, 9, 40)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    Q = rng.standard_normal((T, d)).astype(np.float32); Q /= np.linalg.norm(Q, axis=1, keepdims=True)
+    E = rng.standard_normal((int(off[-1]), d)).astype(np.float32); E /= np.linalg.norm(E, axis=1, keepdims=True)
+    cq, cd = oracle_mod.abs_percentile(Q, 1000), oracle_mod.abs_percentile(E, 1000)
+    assert cq == np.abs(Q).max() and cd == np.abs(E).max()
+    sq, sd = np.float32(cq) / np.float32(127), np.float32(cd) / np.float32(127)
+    H8, _ = oracle_mod.maxsim_cells_i8(oracle_mod.quantize_i8(Q, cq), sq, oracle_mod.quantize_i8(E, cd), sd, off)
+    H = oracle_mod.maxsim_cells(Q, E, off)
+    eq, ed = 0.5 * float(sq) * 1.001, 0.5 * float(sd) * 1.001
+    bound = np.abs(Q).sum(axis=1).max() * ed + np.abs(E).sum(axis=1).max() * eq + d * eq * ed
+    assert np.max(np.abs(H8 - H)) <= bound
+    assert np.max(np.abs(H8 - H)) > 0          # it is an approximation
