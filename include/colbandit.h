@@ -81,6 +81,18 @@ typedef struct {
     int no_cell_cache;  /* nonzero: re-gather the documents in every round instead of
                            caching a small active set's cells at its first gather
                            (test aid; the decisions are the same either way)            */
+    const int8_t *docs_i8;    /* DEVICE [total_tokens][d] int8 codes of doc_tokens, or NULL.
+                                 When given, the elimination rounds run on int8 codes
+                                 (implementation appendix, "Cache-separated quantized
+                                 layout"): every revealed cell is the exact integer
+                                 maximum of <code(q_t), code(e_j)> times the two decode
+                                 scales; the queries are coded by the call itself (per
+                                 query, same scheme).  The survivors are still rescored
+                                 from doc_tokens, so topk_scores keep the exact bits.
+                                 Make the codes with colbandit_quantize_i8.            */
+    const float *docs_scale;  /* DEVICE [1]: decode scale of docs_i8 (required with it)  */
+    int coarse_permille;      /* percentile, in 1/1000, of |Q| at which a query is clipped
+                                 before coding; 0 -> 999 (the paper's 99.9th)            */
     int later_rounds;   /* reveal path of rounds >= 2 for bf16 inputs.  0: chosen on the
                            device each round - one corpus-streaming pass shared by all
                            queries when the active sets are so large that gathering
@@ -128,6 +140,47 @@ size_t colbandit_trace_bytes(int n_queries, int T, int B, int64_t N);
 /* Scratch the two scoring calls need for these sizes (bytes; 0 on invalid sizes). */
 size_t colbandit_workspace_bytes(int n_queries, int T, int d, int64_t N,
                                  int64_t total_tokens, int K, int M);
+
+/*
+ * int8 codes for the coarse elimination pass (implementation appendix, "Cache-separated
+ * quantized layout": clip to the 99.9th percentile of the absolute values, then linear
+ * quantisation to int8).  The input is n_segments consecutive matrices of
+ * rows_per_segment x d values; each segment gets its own clip value: the nearest-rank
+ * percentile of |x|, i.e. the element of rank ceil(n * permille / 1000) of the ascending
+ * order of the segment's n = rows_per_segment * d absolute values (exact, no
+ * interpolation).  code = round-half-even(x * (127 / clip)) saturated to [-127, 127],
+ * evaluated in single precision; scales[s] = clip / 127 decodes segment s.  An all-zero
+ * segment gives zero codes and scale 0.
+ *   x          DEVICE, dtype dt, 16-byte aligned
+ *   permille   1..1000 (999 = the paper's 99.9th percentile)
+ *   codes      DEVICE int8, same shape as x
+ *   scales     DEVICE float [n_segments]
+ *   workspace  DEVICE, 256-byte aligned, >= colbandit_quantize_workspace_bytes(n_segments)
+ * A corpus is one segment (n_segments = 1, rows_per_segment = total_tokens): an
+ * index-time step.  Fully asynchronous.
+ */
+size_t colbandit_quantize_workspace_bytes(int64_t n_segments);
+int colbandit_quantize_i8(const void *x, colbandit_dtype dt, int64_t n_segments,
+                          int64_t rows_per_segment, int d, int permille, int8_t *codes,
+                          float *scales, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+/*
+ * Exhaustive MaxSim on the int8 codes: the coarse cell matrix the elimination rounds of
+ * colbandit_topk see when opts->docs_i8 is given (and a fast approximate scorer).  The
+ * queries are coded by the call (per query, clip at `permille`).
+ *   scores     DEVICE float [n_queries][N]: row sums of the coarse cells
+ *   cells      DEVICE float [n_queries][N][T] or NULL
+ *   q_codes    DEVICE int8 [n_queries][T][d] or NULL: receives the query codes
+ *   q_scales   DEVICE float [n_queries] or NULL: receives their decode scales
+ * Other arguments as for colbandit_full_maxsim (Q and dt are the uncoded queries).
+ */
+int colbandit_coarse_maxsim(const void *Q, int n_queries, int T, int d, colbandit_dtype dt,
+                            const int8_t *docs_i8, const float *docs_scale,
+                            const int64_t *doc_offsets, int64_t N, int64_t total_tokens,
+                            int permille, float *scores, float *cells, int8_t *q_codes,
+                            float *q_scales, void *workspace, size_t workspace_bytes,
+                            void *stream);
 
 /*
  * Exhaustive Full-MaxSim (Eq. (1)-(3)).

@@ -23,7 +23,8 @@ EXPORTS = [
     "colbandit_full_maxsim", "colbandit_topk", "colbandit_workspace_bytes",
     "colbandit_trace_bytes", "colbandit_permutation", "colbandit_radius_prefactor",
     "colbandit_validate_offsets", "colbandit_strerror", "colbandit_sizeof_opts",
-    "colbandit_sizeof_stats",
+    "colbandit_sizeof_stats", "colbandit_quantize_i8", "colbandit_quantize_workspace_bytes",
+    "colbandit_coarse_maxsim",
 ]
 
 
@@ -31,7 +32,9 @@ class ColbanditOpts(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("a", ctypes.c_float), ("b", ctypes.c_float),
                 ("pi", ctypes.c_void_p), ("trace", ctypes.c_void_p),
                 ("trace_bytes", ctypes.c_size_t), ("force_gather", ctypes.c_int),
-                ("no_cell_cache", ctypes.c_int), ("later_rounds", ctypes.c_int)]
+                ("no_cell_cache", ctypes.c_int), ("docs_i8", ctypes.c_void_p),
+                ("docs_scale", ctypes.c_void_p), ("coarse_permille", ctypes.c_int),
+                ("later_rounds", ctypes.c_int)]
 
 
 class ColbanditStats(ctypes.Structure):
@@ -78,6 +81,13 @@ def lib():
         L.colbandit_radius_prefactor.argtypes = [f, f, i, i64, i]
         L.colbandit_validate_offsets.restype = i
         L.colbandit_validate_offsets.argtypes = [vp, i64, i64, vp, sz, vp]
+        L.colbandit_quantize_workspace_bytes.restype = sz
+        L.colbandit_quantize_workspace_bytes.argtypes = [i64]
+        L.colbandit_quantize_i8.restype = i
+        L.colbandit_quantize_i8.argtypes = [vp, i, i64, i64, i, i, vp, vp, vp, sz, vp]
+        L.colbandit_coarse_maxsim.restype = i
+        L.colbandit_coarse_maxsim.argtypes = [vp, i, i, i, i, vp, vp, vp, i64, i64, i, vp, vp, vp, vp,
+                                              vp, sz, vp]
         L.colbandit_sizeof_opts.restype = sz
         L.colbandit_sizeof_opts.argtypes = []
         L.colbandit_sizeof_stats.restype = sz
@@ -115,7 +125,8 @@ def _shapes(Q, docs, offsets):
     if Q.dim() == 2:
         Q = Q.unsqueeze(0)
     assert Q.is_contiguous() and docs.is_contiguous() and offsets.is_contiguous()
-    assert offsets.dtype == torch.int64 and Q.dtype == docs.dtype and Q.shape[2] == docs.shape[1]
+    assert offsets.dtype == torch.int64 and Q.shape[2] == docs.shape[1]
+    assert Q.dtype == docs.dtype or docs.dtype == torch.int8
     nq, T, d = Q.shape
     return Q, nq, T, d, int(offsets.shape[0] - 1), int(docs.shape[0])
 
@@ -182,6 +193,42 @@ def colbandit_full_maxsim(Q, docs, offsets, K=0, want_scores=True, want_cells=Fa
             "phase_ms": (phase[0], phase[1]) if want_phase_ms else None}
 
 
+def colbandit_quantize_i8(x, n_segments=1, permille=999):
+    """int8 codes of x ([rows, d], rows = n_segments * rows_per_segment).  Returns
+    (codes int8 like x, scales float32 [n_segments])."""
+    assert x.is_contiguous() and x.dim() >= 2
+    d = x.shape[-1]
+    rows = x.numel() // d
+    assert rows % n_segments == 0
+    codes = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    scales = torch.empty((n_segments,), dtype=torch.float32, device=x.device)
+    nb = lib().colbandit_quantize_workspace_bytes(n_segments)
+    ws = torch.empty((nb,), dtype=torch.uint8, device=x.device)
+    rc = lib().colbandit_quantize_i8(_ptr(x), _dt(x), n_segments, rows // n_segments, d, int(permille),
+                                     _ptr(codes), _ptr(scales), _ptr(ws), nb, _stream())
+    if rc:
+        raise ColbanditError(rc, "colbandit_quantize_i8")
+    return codes, scales
+
+
+def colbandit_coarse_maxsim(Q, docs_i8, docs_scale, offsets, permille=999, want_cells=False,
+                            workspace=None):
+    """Exhaustive MaxSim on int8 codes.  Returns dict(scores, cells, q_codes, q_scales)."""
+    Q, nq, T, d, N, total = _shapes(Q, docs_i8, offsets)
+    dev = docs_i8.device
+    ws = workspace if workspace is not None else new_workspace(nq, T, d, N, total, dev)
+    scores = torch.empty((nq, N), dtype=torch.float32, device=dev)
+    cells = torch.empty((nq, N, T), dtype=torch.float32, device=dev) if want_cells else None
+    qc = torch.empty((nq, T, d), dtype=torch.int8, device=dev)
+    qs = torch.empty((nq,), dtype=torch.float32, device=dev)
+    rc = lib().colbandit_coarse_maxsim(_ptr(Q), nq, T, d, _dt(Q), _ptr(docs_i8), _ptr(docs_scale),
+                                       _ptr(offsets), N, total, int(permille), _ptr(scores), _ptr(cells),
+                                       _ptr(qc), _ptr(qs), _ptr(ws), ws.numel(), _stream())
+    if rc:
+        raise ColbanditError(rc, "colbandit_coarse_maxsim")
+    return {"scores": scores, "cells": cells, "q_codes": qc, "q_scales": qs}
+
+
 @dataclass
 class Trace:
     count: np.ndarray    # [R+1, nq]
@@ -213,11 +260,14 @@ def _parse_trace(buf: torch.Tensor, nq, T, B, N, queries=None) -> Trace:
 
 def colbandit_topk(Q, docs, offsets, K, alpha_ef=0.2, delta=0.01, M=5, seed=0, B=0, a=0.0, b=0.0,
                    pi=None, trace=False, force_gather=False, want_stats=True, workspace=None,
-                   out=None, no_cell_cache=False, trace_queries=None, later_rounds=0):
+                   out=None, no_cell_cache=False, trace_queries=None, later_rounds=0,
+                   docs_i8=None, docs_scale=None, coarse_permille=0):
     """Col-Bandit top-K.  Returns dict(topk_ids, topk_scores, stats (list of dict) | None,
     trace (Trace) | None).  `pi`: optional int32 device tensor [nq,T]; `trace_queries`: keep
     only these queries' columns of the trace (the device buffer still covers all of them);
-    `later_rounds`: 0 auto, 1 corpus-streaming pass in every round >= 2, 2 always gather."""
+    `later_rounds`: 0 auto, 1 corpus-streaming pass in every round >= 2, 2 always gather;
+    `docs_i8`/`docs_scale` (from colbandit_quantize_i8): run the elimination rounds on int8
+    codes, rescore exactly."""
     Q, nq, T, d, N, total = _shapes(Q, docs, offsets)
     dev = docs.device
     ws = workspace if workspace is not None else new_workspace(nq, T, d, N, total, dev)
@@ -228,7 +278,10 @@ def colbandit_topk(Q, docs, offsets, K, alpha_ef=0.2, delta=0.01, M=5, seed=0, B
         torch.empty((nq, K), dtype=torch.float32, device=dev)
     opts = ColbanditOpts(B=B, a=a, b=b, pi=None, trace=None, trace_bytes=0,
                          force_gather=1 if force_gather else 0,
-                         no_cell_cache=1 if no_cell_cache else 0, later_rounds=int(later_rounds))
+                         no_cell_cache=1 if no_cell_cache else 0, later_rounds=int(later_rounds),
+                         docs_i8=None if docs_i8 is None else docs_i8.data_ptr(),
+                         docs_scale=None if docs_scale is None else docs_scale.data_ptr(),
+                         coarse_permille=int(coarse_permille))
     tbuf = None
     Beff = B if B > 0 else 4
     if pi is not None:

@@ -18,14 +18,14 @@ constexpr int kChunkTokens = 4096;
 
 struct Layout {
     size_t ctl, list0, list1, stat, stat2, pairs, rescored, scores, cnt_hist, tau_hist, pi,
-        chunk_doc, flag, cid, cstat, ccell, total;
+        chunk_doc, flag, cid, cstat, ccell, q8, qscale, qscratch, total;
     int cache_cap, TP;
 };
 
 // Slots per query in the cell cache.
 constexpr int64_t kCacheCapMax = 16384;
 
-Layout make_layout(int nq, int T, int64_t N, int64_t total_tokens) {
+Layout make_layout(int nq, int T, int d, int64_t N, int64_t total_tokens) {
     Layout L{};
     size_t o = 0;
     const size_t qn = (size_t)nq * (size_t)N;
@@ -55,6 +55,9 @@ Layout make_layout(int nq, int T, int64_t N, int64_t total_tokens) {
     L.cid = take(4 * (size_t)nq * L.cache_cap);
     L.cstat = take(8 * (size_t)nq * L.cache_cap);
     L.ccell = take(4 * (size_t)nq * L.cache_cap * L.TP);
+    L.q8 = take((size_t)nq * T * d);                 // int8 codes of the queries
+    L.qscale = take(4 * (size_t)nq);
+    L.qscratch = take(quantize_scratch_bytes(nq));
     L.total = o;
     return L;
 }
@@ -80,6 +83,9 @@ Work carve(void* ws, const Layout& L) {
     W.cid = (int32_t*)(b + L.cid);
     W.cstat = (float2*)(b + L.cstat);
     W.ccell = (float*)(b + L.ccell);
+    W.q8 = (int8_t*)(b + L.q8);
+    W.qscale = (float*)(b + L.qscale);
+    W.qscratch = (void*)(b + L.qscratch);
     return W;
 }
 
@@ -150,10 +156,10 @@ struct PhaseTimer {
 // pair streams its document once (~4.5 TB/s) and nothing is shared between queries.  A
 // gathered visit also caches the document's cells for the remaining rounds when the query fits
 // the cache, so the gather is preferred up to twice the cost of the pass.
-unsigned long long dense_pairs_threshold(const Problem& P, int G) {
-    const double row_bytes = 2.0 * P.d;
+unsigned long long dense_pairs_threshold(const Problem& P, int G, bool codes) {
+    const double row_bytes = (codes ? 1.0 : 2.0) * P.d;   // int8 codes: half the bytes, twice the rate
     const double rows = (double)(((int64_t)P.nq * G + 15) / 16 * 16);
-    const double per_token = fmax(row_bytes / 3.5e12, 2.0 * rows * P.d / 1.15e15);
+    const double per_token = fmax(row_bytes / 3.5e12, 2.0 * rows * P.d / (codes ? 2.3e15 : 1.15e15));
     const double t_pass = (double)P.total * per_token;
     const double t_pair = ((double)P.total / (double)P.N) * row_bytes / 4.5e12;
     const double thr = 2.0 * t_pass / t_pair;
@@ -219,9 +225,9 @@ size_t colbandit_trace_bytes(int n_queries, int T, int B, int64_t N) {
 
 size_t colbandit_workspace_bytes(int n_queries, int T, int d, int64_t N, int64_t total_tokens,
                                  int K, int M) {
-    (void)d; (void)K; (void)M;
+    (void)K; (void)M;
     if (n_queries < 1 || T < 1 || N < 1 || total_tokens < N) return 0;
-    return make_layout(n_queries, T, N, total_tokens).total;
+    return make_layout(n_queries, T, d, N, total_tokens).total;
 }
 
 int colbandit_validate_offsets(const int64_t* doc_offsets, int64_t N, int64_t total_tokens,
@@ -241,6 +247,58 @@ int colbandit_validate_offsets(const int64_t* doc_offsets, int64_t N, int64_t to
     return h ? COLBANDIT_ERR_BAD_OFFSETS : COLBANDIT_OK;
 }
 
+size_t colbandit_quantize_workspace_bytes(int64_t n_segments) {
+    if (n_segments < 1) return 0;
+    return align_up(quantize_scratch_bytes(n_segments));
+}
+
+int colbandit_quantize_i8(const void* x, colbandit_dtype dt, int64_t n_segments,
+                          int64_t rows_per_segment, int d, int permille, int8_t* codes,
+                          float* scales, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!x || !codes || !scales) return COLBANDIT_ERR_NULL;
+    if (n_segments < 1 || n_segments > 65535 || rows_per_segment < 1 || d < 1)
+        return COLBANDIT_ERR_SHAPE;
+    if (dt != COLBANDIT_F32 && dt != COLBANDIT_BF16) return COLBANDIT_ERR_SHAPE;
+    if (permille < 1 || permille > 1000) return COLBANDIT_ERR_KNOB;
+    if (rows_per_segment > (int64_t)0x7fffffffffffLL / d) return COLBANDIT_ERR_UNSUPPORTED;
+    if (((uintptr_t)x & 15) || ((uintptr_t)scales & 3)) return COLBANDIT_ERR_ALIGNMENT;
+    int rc = check_workspace(workspace, workspace_bytes, colbandit_quantize_workspace_bytes(n_segments));
+    if (rc) return rc;
+    const hipError_t e = launch_quantize_i8(x, (int)dt, n_segments, rows_per_segment * d, permille,
+                                            codes, scales, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? COLBANDIT_OK : COLBANDIT_ERR_HIP;
+}
+
+int colbandit_coarse_maxsim(const void* Q, int n_queries, int T, int d, colbandit_dtype dt,
+                            const int8_t* docs_i8, const float* docs_scale,
+                            const int64_t* doc_offsets, int64_t N, int64_t total_tokens,
+                            int permille, float* scores, float* cells, int8_t* q_codes,
+                            float* q_scales, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+    int rc = check_shapes(Q, n_queries, T, d, (int)dt, docs_i8, doc_offsets, N, total_tokens);
+    if (rc) return rc;
+    if (!docs_scale || !scores) return COLBANDIT_ERR_NULL;
+    if (permille < 1 || permille > 1000) return COLBANDIT_ERR_KNOB;
+    const Layout L = make_layout(n_queries, T, d, N, total_tokens);
+    rc = check_workspace(workspace, workspace_bytes, L.total);
+    if (rc) return rc;
+    const Work W = carve(workspace, L);
+    const Problem P{Q, n_queries, T, d, (int)dt, docs_i8, doc_offsets, N, total_tokens};
+    hipStream_t st = (hipStream_t)stream;
+    Coarse co{docs_i8, docs_scale, W.q8, W.qscale};
+    if (!dense_supported(P, &co)) return COLBANDIT_ERR_UNSUPPORTED;
+    hipError_t e = launch_quantize_i8(Q, (int)dt, n_queries, (int64_t)T * d, permille, W.q8,
+                                      W.qscale, W.qscratch, st);
+    int n_chunks = 0;
+    if (e == hipSuccess) e = launch_dense_prepare(P, W, kChunkTokens, &n_chunks, st);
+    if (e == hipSuccess) e = launch_dense_score(P, W, kChunkTokens, n_chunks, scores, cells, &co, st);
+    if (e == hipSuccess && q_codes)
+        e = hipMemcpyAsync(q_codes, W.q8, (size_t)n_queries * T * d, hipMemcpyDeviceToDevice, st);
+    if (e == hipSuccess && q_scales)
+        e = hipMemcpyAsync(q_scales, W.qscale, sizeof(float) * n_queries, hipMemcpyDeviceToDevice, st);
+    return e == hipSuccess ? COLBANDIT_OK : COLBANDIT_ERR_HIP;
+}
+
 size_t colbandit_sizeof_opts(void) { return sizeof(colbandit_opts); }
 size_t colbandit_sizeof_stats(void) { return sizeof(colbandit_stats); }
 
@@ -255,7 +313,7 @@ int colbandit_full_maxsim(const void* Q, int n_queries, int T, int d, colbandit_
     if (K > COLBANDIT_MAX_K) return COLBANDIT_ERR_UNSUPPORTED;
     if (K == 0 && !scores) return COLBANDIT_ERR_NULL;
     if (K > 0 && (!topk_ids || !topk_scores)) return COLBANDIT_ERR_NULL;
-    const Layout L = make_layout(n_queries, T, N, total_tokens);
+    const Layout L = make_layout(n_queries, T, d, N, total_tokens);
     rc = check_workspace(workspace, workspace_bytes, L.total);
     if (rc) return rc;
 
@@ -272,14 +330,15 @@ int colbandit_full_maxsim(const void* Q, int n_queries, int T, int d, colbandit_
     };
     hipError_t e = hipSuccess;
     mark();
-    if (dense_supported(P)) {
+    if (dense_supported(P, nullptr)) {
         int n_chunks = 0;
         e = launch_dense_prepare(P, W, kChunkTokens, &n_chunks, st);
         mark();
-        if (e == hipSuccess) e = launch_dense_score(P, W, kChunkTokens, n_chunks, out, cells, st);
+        if (e == hipSuccess)
+            e = launch_dense_score(P, W, kChunkTokens, n_chunks, out, cells, nullptr, st);
     } else {
         mark();
-        e = launch_gather_score(P, W, false, out, cells, st);
+        e = launch_gather_score(P, W, false, out, cells, false, st);
     }
     mark();
     if (e == hipSuccess && K > 0) e = launch_topk(P, W, false, out, K, topk_ids, topk_scores, st);
@@ -317,6 +376,8 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
     size_t trace_bytes = 0;
     bool force_gather = false, no_cache = false;
     int later_rounds = 0;
+    Coarse coarse{};
+    int q_permille = 999;
     if (opts) {
         if (opts->B < 0) return COLBANDIT_ERR_KNOB;
         if (opts->B > 0) kn.B = opts->B;
@@ -332,11 +393,20 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
         no_cache = opts->no_cell_cache != 0;
         if (opts->later_rounds < 0 || opts->later_rounds > 2) return COLBANDIT_ERR_KNOB;
         later_rounds = opts->later_rounds;
+        if (opts->docs_i8) {
+            if (!opts->docs_scale) return COLBANDIT_ERR_NULL;
+            if (((uintptr_t)opts->docs_i8 & 15) || ((uintptr_t)opts->docs_scale & 3))
+                return COLBANDIT_ERR_ALIGNMENT;
+            if (opts->coarse_permille < 0 || opts->coarse_permille > 1000) return COLBANDIT_ERR_KNOB;
+            if (opts->coarse_permille > 0) q_permille = opts->coarse_permille;
+            coarse.docs8 = opts->docs_i8;
+            coarse.dscale = opts->docs_scale;
+        }
     }
     if (kn.B > COLBANDIT_MAX_B) return COLBANDIT_ERR_UNSUPPORTED;
     const int R = (T + kn.B - 1) / kn.B;
     if (R > COLBANDIT_MAX_ROUNDS) return COLBANDIT_ERR_UNSUPPORTED;
-    const Layout L = make_layout(n_queries, T, N, total_tokens);
+    const Layout L = make_layout(n_queries, T, d, N, total_tokens);
     rc = check_workspace(workspace, workspace_bytes, L.total);
     if (rc) return rc;
 
@@ -367,7 +437,17 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
 
     hipError_t e = launch_init(P, W, kn, R, seed, user_pi, tr, st);
     const bool loop = N > (int64_t)K + M;    // |A_1| > K + M, else the loop body never runs
-    const bool dense = dense_supported(P) && !force_gather;
+    // coarse pass: code the queries (per query) and reveal from the int8 codes
+    const Coarse* co = nullptr;
+    if (coarse.docs8) {
+        coarse.Q8 = W.q8;
+        coarse.qscale = W.qscale;
+        co = &coarse;
+        if (e == hipSuccess && loop)
+            e = launch_quantize_i8(Q, (int)dt, n_queries, (int64_t)T * d, q_permille, W.q8,
+                                   W.qscale, W.qscratch, st);
+    }
+    const bool dense = dense_supported(P, co) && !force_gather;
     int n_chunks = 0;
     if (e == hipSuccess && loop && dense) e = launch_dense_prepare(P, W, kChunkTokens, &n_chunks, st);
     for (int r = 1; e == hipSuccess && loop && r <= R; ++r) {
@@ -383,20 +463,21 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
         while (G < rr.nb) G <<= 1;
         rr.dense_thr = ~0ull;
         if (r == 1 && dense) {
-            e = launch_dense_reveal(P, W, kChunkTokens, n_chunks, rr, G, st);
+            e = launch_dense_reveal(P, W, kChunkTokens, n_chunks, rr, G, co, st);
         } else {
             if (r >= 2 && dense && later_rounds != 2)
-                rr.dense_thr = later_rounds == 1 ? 0ull : dense_pairs_threshold(P, G);
-            e = launch_dense_reveal_later(P, W, kChunkTokens, n_chunks, rr, G, st);
-            if (e == hipSuccess) e = launch_gather_reveal(P, W, rr, st);
-            if (e == hipSuccess && r >= 2) e = launch_gather_cells(P, W, rr, st);
+                rr.dense_thr = later_rounds == 1 ? 0ull : dense_pairs_threshold(P, G, co != nullptr);
+            e = launch_dense_reveal_later(P, W, kChunkTokens, n_chunks, rr, G, co, st);
+            if (e == hipSuccess) e = launch_gather_reveal(P, W, rr, co, st);
+            if (e == hipSuccess && r >= 2) e = launch_gather_cells(P, W, rr, co, st);
         }
         pt.mark(r == 1 ? PH_FIRST_REVEAL : PH_LATER_REVEAL);
         if (e == hipSuccess) e = launch_select_prune(P, W, kn, rr, tr, st);
         pt.mark(PH_SELECT);
     }
-    if (e == hipSuccess) e = launch_gather_score(P, W, true, W.rescored, nullptr, st);
-    if (e == hipSuccess) e = launch_cached_score(P, W, W.rescored, st);
+    // exact rescore from the stored embeddings; cached cells give it only when they are exact
+    if (e == hipSuccess) e = launch_gather_score(P, W, true, W.rescored, nullptr, co != nullptr, st);
+    if (e == hipSuccess && !co) e = launch_cached_score(P, W, W.rescored, st);
     if (e == hipSuccess) e = launch_topk(P, W, true, W.rescored, K, topk_ids, topk_scores, st);
     pt.mark(PH_RESCORE);
     if (e != hipSuccess) {

@@ -48,13 +48,21 @@ struct DenseArgs {
     const unsigned long long* pairs_r;
     unsigned long long dense_thr;
     const QueryCtl* ctl;
+    // int8 codes: a cell is the integer maximum times qscale[q] * dscale[0]
+    const float* qscale;
+    const float* dscale;
 };
 
-template <int D, int NT, int TQ, bool REVEAL>
+template <typename Tag, int D, int NT, int TQ, bool REVEAL>
 __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
-    using F = Frag<bf16_tag, D>;
-    constexpr int ROWB = D * 2;            // bytes per token row
+    using F = Frag<Tag, D>;
+    using V = typename F::val_t;           // float, or int for int8 codes
+    constexpr bool CODES = !__is_same(V, float);
+    constexpr int ROWB = D * F::ELEM_BYTES;   // bytes per token row
     constexpr int NCH = ROWB / 16;         // 16-byte pieces per row
+    // Swizzle key of a ring row: rows whose 16-byte pieces would fall on the same banks
+    // (row stride ROWB against the 256-byte bank window) get different keys.
+    constexpr int KEY_SHIFT = NCH >= 16 ? 0 : (NCH == 8 ? 1 : 2);
     __shared__ __attribute__((aligned(16))) char ring[RING_ROWS * ROWB];
 
     const int lane = threadIdx.x & 63;
@@ -117,7 +125,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
             if (rbase < ntok) {
                 const int lrow = rbase + lane / NCH;                  // the LDS row this lane fills
                 const int grow = lrow < ntok ? lrow : ntok - 1;       // rows past the end are never read
-                const int c = (lane & (NCH - 1)) ^ (lrow & (NCH - 1));
+                const int c = (lane & (NCH - 1)) ^ ((lrow >> KEY_SHIFT) & (NCH - 1));
                 __builtin_amdgcn_global_load_lds(
                     (const __attribute__((address_space(1))) void*)(src + (size_t)grow * ROWB + c * 16),
                     (__attribute__((address_space(3))) void*)(ring + (rbase & (RING_ROWS - 1)) * ROWB),
@@ -146,9 +154,22 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
         return __builtin_amdgcn_readlane(offv, i - ibase);
     };
 
-    float h[NT];
+    V h[NT];
 #pragma unroll
-    for (int tt = 0; tt < NT; ++tt) h[tt] = -__builtin_inff();
+    for (int tt = 0; tt < NT; ++tt) h[tt] = lowest_val<V>();
+
+    // int8 codes: decode scale of the query behind each of this lane's packed results
+    float cscale[Pack<NT>::NW];
+    if constexpr (CODES) {
+        const float ds = A.dscale[0];
+#pragma unroll
+        for (int j = 0; j < Pack<NT>::NW; ++j) {
+            const int g = tile0 + Pack<NT>::tile_of_row(j, lane >> 4);
+            int q = REVEAL ? (g * 16 + col) / A.G : g / TQ;
+            q = q < A.nq ? q : 0;
+            cscale[j] = A.qscale[q] * ds;
+        }
+    }
 
     // reveal: which of this lane's result registers belong to a query that takes the batch
     unsigned qmask = ~0u;
@@ -171,10 +192,18 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
     // per-document epilogue: cross-lane maxima, then the row sum (score) or the batch
     // statistics (reveal), written by the lanes that own a query
     auto finalize = [&](int doc) {
-        if constexpr (REVEAL) {
-            using P = Pack<NT>;
-            float w[P::NW];
+        using P = Pack<NT>;
+        // cross-lane column maxima, decoded to float cells
+        float w[P::NW];
+        if constexpr (CODES) {
+            V wi[P::NW];
+            P::colmax(h, wi);
+#pragma unroll
+            for (int j = 0; j < P::NW; ++j) w[j] = (float)wi[j] * cscale[j];
+        } else {
             P::colmax(h, w);
+        }
+        if constexpr (REVEAL) {
             const int row = lane >> 4;
 #pragma unroll
             for (int j = 0; j < P::NW; ++j) {
@@ -187,8 +216,8 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
             }
         } else {
             using SC = Score<NT, TQ>;
-            float w[SC::NW], sc[SC::NS];
-            SC::run(h, A.T, col, w, sc);
+            float sc[SC::NS];
+            SC::finish(w, A.T, col, sc);
 #pragma unroll
             for (int j = 0; j < SC::NS; ++j) {
                 const int lq = SC::writer(j, lane);
@@ -207,7 +236,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
             }
         }
 #pragma unroll
-        for (int tt = 0; tt < NT; ++tt) h[tt] = -__builtin_inff();
+        for (int tt = 0; tt < NT; ++tt) h[tt] = lowest_val<V>();
     };
 
     // one block of 16 tokens against all NT column tiles
@@ -258,10 +287,12 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
         int row = (start & 1) ? ((col == 0) ? start + 15 : start - 1 + col) : start + col;
         row = row < end ? row : end - 1;
         const char* rp = ring + (row & (RING_ROWS - 1)) * ROWB;
-        const int sw = row & (NCH - 1);
+        const int sw = (row >> KEY_SHIFT) & (NCH - 1);
 #pragma unroll
-        for (int ks = 0; ks < F::KS; ++ks)
-            a.v[ks] = *(const bf16x8_t*)(rp + (((ks * 4 + kg) ^ sw) * 16));
+        for (int ks = 0; ks < F::KS; ++ks) {
+            using piece_t = __remove_reference_t(decltype(a.v[0]));
+            a.v[ks] = *(const piece_t*)(rp + (((ks * 4 + kg) ^ sw) * 16));
+        }
         lcur = end;
         return BlockInfo{ldoc, end == lend};
     };
@@ -307,8 +338,10 @@ __global__ void k_chunk_docs(const int64_t* off, int64_t N, int C, int n_chunks,
     for (int64_t c = lo; c <= hi; ++c) chunk_doc[c] = (int32_t)i;
 }
 
-bool dense_supported(const Problem& P) {
-    return P.dt == DT_BF16 && (P.d == 64 || P.d == 128) && P.total / 4096 < 0x7fffff00;
+bool dense_supported(const Problem& P, const Coarse* co) {
+    // the streaming kernel reads bf16 embeddings or int8 codes
+    return (P.dt == DT_BF16 || co != nullptr) && (P.d == 64 || P.d == 128) &&
+           P.total / 4096 < 0x7fffff00;
 }
 
 hipError_t launch_dense_prepare(const Problem& P, const Work& W, int C, int* n_chunks,
@@ -334,68 +367,89 @@ static void fill_dense(DenseArgs& A, const Problem& P, const Work& W, int n_chun
     A.stat = W.stat;
 }
 
-template <int D, int NT, int TQ, bool REVEAL>
+template <typename Tag, int D, int NT, int TQ, bool REVEAL>
 static hipError_t dense_go(DenseArgs& A, int tiles, hipStream_t st) {
     A.n_groups = (tiles + 4 * NT - 1) / (4 * NT);
     const int chunks8 = (A.n_chunks + 7) / 8 * 8;
     const long long blocks = (long long)chunks8 * A.n_groups;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    k_dense<D, NT, TQ, REVEAL><<<(unsigned)blocks, DENSE_THREADS, 0, st>>>(A);
+    k_dense<Tag, D, NT, TQ, REVEAL><<<(unsigned)blocks, DENSE_THREADS, 0, st>>>(A);
     return hipGetLastError();
 }
 
-template <int D, int TQ>
+template <typename Tag, int D, int TQ>
 static hipError_t dense_score_nt(DenseArgs& A, int tiles, hipStream_t st) {
     if constexpr (TQ <= 2) {
-        if (tiles <= 8) return dense_go<D, 2, TQ, false>(A, tiles, st);
+        if (tiles <= 8) return dense_go<Tag, D, 2, TQ, false>(A, tiles, st);
     }
     if constexpr (TQ <= 4) {
-        if (tiles <= 16) return dense_go<D, 4, TQ, false>(A, tiles, st);
+        if (tiles <= 16) return dense_go<Tag, D, 4, TQ, false>(A, tiles, st);
     }
-    return dense_go<D, 8, TQ, false>(A, tiles, st);
+    return dense_go<Tag, D, 8, TQ, false>(A, tiles, st);
 }
 
-template <int D>
+template <typename Tag, int D>
 static hipError_t dense_score_d(DenseArgs& A, hipStream_t st) {
     const int tq = (A.T + 15) / 16;
-    if (tq <= 1) return dense_score_nt<D, 1>(A, A.nq * 1, st);
-    if (tq <= 2) return dense_score_nt<D, 2>(A, A.nq * 2, st);
-    if (tq <= 4) return dense_score_nt<D, 4>(A, A.nq * 4, st);
-    return dense_score_nt<D, 8>(A, A.nq * 8, st);
+    if (tq <= 1) return dense_score_nt<Tag, D, 1>(A, A.nq * 1, st);
+    if (tq <= 2) return dense_score_nt<Tag, D, 2>(A, A.nq * 2, st);
+    if (tq <= 4) return dense_score_nt<Tag, D, 4>(A, A.nq * 4, st);
+    return dense_score_nt<Tag, D, 8>(A, A.nq * 8, st);
+}
+
+// int8 codes instead of the stored embeddings
+static void use_codes(DenseArgs& A, const Coarse* co) {
+    A.Q = co->Q8;
+    A.docs = co->docs8;
+    A.qscale = co->qscale;
+    A.dscale = co->dscale;
 }
 
 hipError_t launch_dense_score(const Problem& P, const Work& W, int C, int n_chunks, float* out,
-                              float* cells, hipStream_t st) {
+                              float* cells, const Coarse* co, hipStream_t st) {
     (void)C;
     DenseArgs A{};
     fill_dense(A, P, W, n_chunks);
     A.out = out;
     A.cells = cells;
-    return P.d == 128 ? dense_score_d<128>(A, st) : dense_score_d<64>(A, st);
+    if (co) {
+        use_codes(A, co);
+        return P.d == 128 ? dense_score_d<i8_tag, 128>(A, st) : dense_score_d<i8_tag, 64>(A, st);
+    }
+    return P.d == 128 ? dense_score_d<bf16_tag, 128>(A, st) : dense_score_d<bf16_tag, 64>(A, st);
 }
 
-template <int D>
+template <typename Tag, int D>
 static hipError_t dense_reveal_d(DenseArgs& A, hipStream_t st) {
     const int tiles = (A.nq * A.G + 15) / 16;
-    if (tiles <= 4) return dense_go<D, 1, 1, true>(A, tiles, st);
-    if (tiles <= 8) return dense_go<D, 2, 1, true>(A, tiles, st);
-    if (tiles <= 16) return dense_go<D, 4, 1, true>(A, tiles, st);
-    return dense_go<D, 8, 1, true>(A, tiles, st);
+    if (tiles <= 4) return dense_go<Tag, D, 1, 1, true>(A, tiles, st);
+    if (tiles <= 8) return dense_go<Tag, D, 2, 1, true>(A, tiles, st);
+    if (tiles <= 16) return dense_go<Tag, D, 4, 1, true>(A, tiles, st);
+    return dense_go<Tag, D, 8, 1, true>(A, tiles, st);
+}
+
+static hipError_t dense_reveal_any(DenseArgs& A, const Problem& P, const Coarse* co, hipStream_t st) {
+    if (co) {
+        use_codes(A, co);
+        return P.d == 128 ? dense_reveal_d<i8_tag, 128>(A, st) : dense_reveal_d<i8_tag, 64>(A, st);
+    }
+    return P.d == 128 ? dense_reveal_d<bf16_tag, 128>(A, st) : dense_reveal_d<bf16_tag, 64>(A, st);
 }
 
 hipError_t launch_dense_reveal(const Problem& P, const Work& W, int C, int n_chunks,
-                               const RevealRound& rr, int G, hipStream_t st) {
+                               const RevealRound& rr, int G, const Coarse* co, hipStream_t st) {
     (void)C;
     DenseArgs A{};
     fill_dense(A, P, W, n_chunks);
     A.lo = rr.lo;
     A.nb = rr.nb;
     A.G = G;
-    return P.d == 128 ? dense_reveal_d<128>(A, st) : dense_reveal_d<64>(A, st);
+    return dense_reveal_any(A, P, co, st);
 }
 
 hipError_t launch_dense_reveal_later(const Problem& P, const Work& W, int C, int n_chunks,
-                                     const RevealRound& rr, int G, hipStream_t st) {
+                                     const RevealRound& rr, int G, const Coarse* co,
+                                     hipStream_t st) {
     (void)C;
     if (rr.dense_thr == ~0ull) return hipSuccess;
     DenseArgs A{};
@@ -407,7 +461,7 @@ hipError_t launch_dense_reveal_later(const Problem& P, const Work& W, int C, int
     A.pairs_r = W.pairs + rr.r;
     A.dense_thr = rr.dense_thr;
     A.ctl = W.ctl;
-    return P.d == 128 ? dense_reveal_d<128>(A, st) : dense_reveal_d<64>(A, st);
+    return dense_reveal_any(A, P, co, st);
 }
 
 }  // namespace cb

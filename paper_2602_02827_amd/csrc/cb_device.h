@@ -14,11 +14,14 @@ namespace cb {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 // `wide`: up to 8 column tiles (T <= 128) fit the register file; fp32 stops at 4.
 struct bf16_tag { static constexpr bool wide = true; };
 struct f32_tag { static constexpr bool wide = false; };
+// int8 codes of the coarse elimination pass (implementation appendix, quantized layout)
+struct i8_tag { static constexpr bool wide = true; };
 
 // Per-query round control, resident in the workspace.  `implicit` means the active set
 // is still all N documents in index order (no list has been written yet).
@@ -49,12 +52,17 @@ __device__ __forceinline__ bool dense_round(const unsigned long long* pairs_r,
 //   fp32: v_mfma_f32_16x16x4_f32; the lane loads 16 bytes = k in
 //         [16j + 4*(lane>>4), +4) and feeds component e to the e-th instruction of
 //         group j, i.e. instruction (j,e) contracts k = 16j + 4g + e over g = 0..3.
+//   int8: v_mfma_i32_16x16x64_i8, k-step s covers k in [64s, 64s+64); the lane holds
+//         k = 64s + 16*(lane>>4) .. +15 (one 16-byte load); int32 accumulation is exact.
+// acc_t / val_t: accumulator vector and the scalar type of a cell before decoding.
 // ---------------------------------------------------------------------------------
 template <typename Tag, int D> struct Frag;
 
 template <int D> struct Frag<bf16_tag, D> {
     static constexpr int KS = D / 32;
     static constexpr int ELEM_BYTES = 2;
+    using acc_t = f32x4_t;
+    using val_t = float;
     bf16x8_t v[KS];
     __device__ __forceinline__ void load(const void* row, int kgroup) {
         const char* p = (const char*)row + kgroup * 16;
@@ -80,6 +88,8 @@ template <int D> struct Frag<bf16_tag, D> {
 template <int D> struct Frag<f32_tag, D> {
     static constexpr int KS = D / 16;
     static constexpr int ELEM_BYTES = 4;
+    using acc_t = f32x4_t;
+    using val_t = float;
     f32x4_t v[KS];
     __device__ __forceinline__ void load(const void* row, int kgroup) {
         const char* p = (const char*)row + kgroup * 16;
@@ -107,6 +117,38 @@ template <int D> struct Frag<f32_tag, D> {
     }
 };
 
+template <int D> struct Frag<i8_tag, D> {
+    static constexpr int KS = D / 64;
+    static constexpr int ELEM_BYTES = 1;
+    using acc_t = i32x4_t;
+    using val_t = int;
+    i32x4_t v[KS];
+    __device__ __forceinline__ void load(const void* row, int kgroup) {
+        const char* p = (const char*)row + kgroup * 16;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) v[s] = *(const i32x4_t*)(p + s * 64);
+    }
+    __device__ __forceinline__ static void mma(i32x4_t& acc, const Frag& a, const Frag& b) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a.v[s], b.v[s], acc, 0, 0, 0);
+    }
+    __device__ __forceinline__ static void mma2(i32x4_t& c0, i32x4_t& c1, const Frag& a,
+                                                const Frag& b0, const Frag& b1) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            c0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a.v[s], b0.v[s], c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a.v[s], b1.v[s], c1, 0, 0, 0);
+        }
+    }
+};
+
+// "no token seen yet" for a running maximum
+template <class V> __device__ __forceinline__ V lowest_val();
+template <> __device__ __forceinline__ float lowest_val<float>() { return -__builtin_inff(); }
+template <> __device__ __forceinline__ int lowest_val<int>() { return (int)0x80000000; }
+__device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
+
 // Accumulator layout of the 16x16 MFMAs: lane holds column (lane & 15) and rows
 // 4*(lane >> 4) + {0,1,2,3}.  Rows are document tokens, columns are query rows.
 __device__ __forceinline__ float max4(const f32x4_t& c) {
@@ -118,21 +160,28 @@ __device__ __forceinline__ float fold_max(float h, const f32x4_t& c) {
     return fmaxf(fmaxf(h, t), c[3]);
 }
 
+__device__ __forceinline__ int fold_max(int h, const i32x4_t& c) {
+    const int t = imax(imax(c[0], c[1]), c[2]);
+    return imax(imax(h, t), c[3]);
+}
+
 // One block of 16 document tokens against NT column tiles, folded into the running
 // maxima h.  Tiles go in pairs: the two accumulation chains of a pair are interleaved
 // (no back-to-back dependent MFMAs) and a pair's maxima are taken while the next pair's
 // MFMAs run.
 template <int NT, class F>
-__device__ __forceinline__ void block_mma(const F& a, const F (&bq)[NT], float (&h)[NT]) {
+__device__ __forceinline__ void block_mma(const F& a, const F (&bq)[NT],
+                                          typename F::val_t (&h)[NT]) {
+    using acc_t = typename F::acc_t;
     if constexpr (NT == 1) {
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        acc_t acc = {0, 0, 0, 0};
         F::mma(acc, a, bq[0]);
         h[0] = fold_max(h[0], acc);
     } else {
-        f32x4_t p0 = {0.f, 0.f, 0.f, 0.f}, p1 = p0;
+        acc_t p0 = {0, 0, 0, 0}, p1 = p0;
 #pragma unroll
         for (int p = 0; p < NT / 2; ++p) {
-            f32x4_t c0 = {0.f, 0.f, 0.f, 0.f}, c1 = c0;
+            acc_t c0 = {0, 0, 0, 0}, c1 = c0;
             F::mma2(c0, c1, a, bq[2 * p], bq[2 * p + 1]);
             if (p > 0) {
                 h[2 * p - 2] = fold_max(h[2 * p - 2], p0);
@@ -184,6 +233,16 @@ __device__ __forceinline__ float maxpack32(float a, float b) {
 __device__ __forceinline__ float maxpack16(float a, float b) {
     swap16(a, b);
     return fmaxf(a, b);
+}
+__device__ __forceinline__ int maxpack32(int a, int b) {
+    auto r = __builtin_amdgcn_permlane32_swap((unsigned)a, (unsigned)b, false, false);
+    const unsigned r0 = r[0], r1 = r[1];
+    return imax((int)r0, (int)r1);
+}
+__device__ __forceinline__ int maxpack16(int a, int b) {
+    auto r = __builtin_amdgcn_permlane16_swap((unsigned)a, (unsigned)b, false, false);
+    const unsigned r0 = r[0], r1 = r[1];
+    return imax((int)r0, (int)r1);
 }
 // every lane <- w[lane] + w[lane ^ 32] (lower-row operand first in every lane)
 __device__ __forceinline__ float addswap32(float w) {
@@ -240,18 +299,19 @@ template <int NT> struct Pack {
         if (NT == 2) return (row & 1) == 0;
         return row == 0;
     }
-    __device__ __forceinline__ static void colmax(const float (&h)[NT], float (&w)[NW]) {
+    template <class V>
+    __device__ __forceinline__ static void colmax(const V (&h)[NT], V (&w)[NW]) {
         if constexpr (NT == 1) {
-            const float m = maxpack32(h[0], h[0]);
+            const V m = maxpack32(h[0], h[0]);
             w[0] = maxpack16(m, m);
         } else if constexpr (NT == 2) {
-            const float m = maxpack32(h[0], h[1]);
+            const V m = maxpack32(h[0], h[1]);
             w[0] = maxpack16(m, m);
         } else {
 #pragma unroll
             for (int j = 0; j < NW; ++j) {
-                const float m0 = maxpack32(h[4 * j], h[4 * j + 1]);
-                const float m1 = maxpack32(h[4 * j + 2], h[4 * j + 3]);
+                const V m0 = maxpack32(h[4 * j], h[4 * j + 1]);
+                const V m1 = maxpack32(h[4 * j + 2], h[4 * j + 3]);
                 w[j] = maxpack16(m0, m1);
             }
         }
@@ -270,12 +330,18 @@ template <int NT, int TQ> struct Score {
     static constexpr int NS = TQ == 8 ? 1 : NW;
     __device__ __forceinline__ static void run(float (&h)[NT], int T, int col, float (&w)[NW],
                                                float (&s)[NS]) {
-        if (T != TQ * 16) {
-#pragma unroll
-            for (int tt = 0; tt < NT; ++tt)
-                if ((tt % TQ) * 16 + col >= T) h[tt] = 0.f;
-        }
         P::colmax(h, w);
+        finish(w, T, col, s);
+    }
+    // the same from packed cells (row r of w[j] = tile tile_of_row(j, r)); columns that are
+    // not query tokens are zeroed in w
+    __device__ __forceinline__ static void finish(float (&w)[NW], int T, int col, float (&s)[NS]) {
+        if (T != TQ * 16) {
+            const int row = (int)(threadIdx.x & 63) >> 4;
+#pragma unroll
+            for (int j = 0; j < NW; ++j)
+                if ((P::tile_of_row(j, row) % TQ) * 16 + col >= T) w[j] = 0.f;
+        }
         if constexpr (TQ == 1) {
 #pragma unroll
             for (int j = 0; j < NW; ++j) s[j] = rowsum16(w[j]);

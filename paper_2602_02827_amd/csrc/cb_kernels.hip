@@ -131,11 +131,17 @@ struct GatherArgs {
     // score
     float* out;
     float* cells;
+    int score_slots;          // GM_SCORE: also serve queries whose list holds cache slots
+    // int8 codes: a cell is the integer maximum times qscale[q] * dscale[0]
+    const float* qscale;
+    const float* dscale;
 };
 
 template <typename Tag, int D, int TQ, int MODE>
 __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
     using F = Frag<Tag, D>;
+    using V = typename F::val_t;
+    constexpr bool CODES = !__is_same(V, float);
     const int q = blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -145,10 +151,12 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
 
     int count = (int)A.N;
     int32_t* list = nullptr;
+    const int32_t* slot_ids = nullptr;      // list entries are cache slots: slot -> document id
     if (MODE != GM_SCORE && dense_round(A.pairs_r, A.dense_thr)) return;   // the dense pass serves it
     if (A.ctl) {
         const QueryCtl c = A.ctl[q];
-        if (c.mode != 0) return;
+        if (c.mode != 0 && !(MODE == GM_SCORE && A.score_slots)) return;
+        if (c.mode != 0) slot_ids = A.cid + (size_t)q * A.cache_cap;
         if (MODE != GM_SCORE && !c.active) return;
         const bool cacheable = !c.implicit && c.count <= A.cache_cap;
         if (MODE == GM_REVEAL && cacheable) return;
@@ -176,14 +184,15 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
 
     const int stride = gridDim.x * 4;
     for (int k = first; k < count; k += stride) {
-        const int id = list ? list[k] : k;
+        int id = list ? list[k] : k;
+        if (slot_ids) id = slot_ids[id];
         int64_t o0 = A.off[id], o1 = A.off[id + 1];
         o0 = o0 < 0 ? 0 : (o0 > A.total ? A.total : o0);
         o1 = o1 < o0 ? o0 : (o1 > A.total ? A.total : o1);
 
-        float h[TQ];
+        V h[TQ];
 #pragma unroll
-        for (int tt = 0; tt < TQ; ++tt) h[tt] = -__builtin_inff();
+        for (int tt = 0; tt < TQ; ++tt) h[tt] = lowest_val<V>();
 
         for (int64_t r0 = o0; r0 < o1; r0 += 16) {
             int64_t row = r0 + col;
@@ -192,15 +201,27 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
             a.load((const char*)A.docs + (size_t)row * row_bytes, kg);
 #pragma unroll
             for (int tt = 0; tt < TQ; ++tt) {
-                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+                typename F::acc_t acc = {0, 0, 0, 0};
                 F::mma(acc, a, bq[tt]);
                 h[tt] = fold_max(h[tt], acc);
             }
         }
 
+        // cross-lane column maxima, decoded to float cells
+        constexpr int NWQ = Pack<MODE == GM_REVEAL ? 1 : TQ>::NW;
+        float w[NWQ];
+        if constexpr (CODES) {
+            V wi[NWQ];
+            Pack<MODE == GM_REVEAL ? 1 : TQ>::colmax(h, wi);
+            const float scale = A.qscale[q] * A.dscale[0];
+#pragma unroll
+            for (int j = 0; j < NWQ; ++j) w[j] = (float)wi[j] * scale;
+        } else {
+            Pack<MODE == GM_REVEAL ? 1 : TQ>::colmax(h, w);
+        }
+
         if constexpr (MODE == GM_REVEAL) {
-            float w[1], sb, m2b;
-            Pack<1>::colmax(h, w);
+            float sb, m2b;
             batch_stats(w[0], col % A.G, A.nb, A.G, sb, m2b);
             if (lane == 0) {
                 const size_t x = (size_t)q * A.N + id;
@@ -211,8 +232,6 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
             }
         } else if constexpr (MODE == GM_CELLS) {
             using P = Pack<TQ>;
-            float w[P::NW];
-            P::colmax(h, w);
             const int row = lane >> 4;
             const size_t slot = (size_t)q * A.cache_cap + k;
             float* crow = A.ccell + slot * A.TP;
@@ -240,8 +259,8 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
             }
         } else {
             using SC = Score<TQ, TQ>;
-            float w[SC::NW], sc[SC::NS];
-            SC::run(h, A.T, col, w, sc);
+            float sc[SC::NS];
+            SC::finish(w, A.T, col, sc);
             if (lane == 0) A.out[(size_t)q * A.N + (A.ctl ? k : id)] = sc[0];
             if (A.cells) {
                 const int row = lane >> 4;
@@ -319,36 +338,48 @@ static void fill_round(GatherArgs& A, const Work& W, const RevealRound& rr) {
     while (A.G < rr.nb) A.G <<= 1;
 }
 
+// co != nullptr: the reveal reads the int8 codes instead of the stored embeddings
+static hipError_t gather_any(GatherArgs& A, int mode, const Problem& P, int64_t max_count,
+                             const Coarse* co, hipStream_t st) {
+    if (co) {
+        A.Q = co->Q8;
+        A.docs = co->docs8;
+        A.qscale = co->qscale;
+        A.dscale = co->dscale;
+        return gather_by_d<i8_tag>(A, mode, P, max_count, st);
+    }
+    return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, mode, P, max_count, st)
+                           : gather_by_d<f32_tag>(A, mode, P, max_count, st);
+}
+
 hipError_t launch_gather_reveal(const Problem& P, const Work& W, const RevealRound& rr,
-                                hipStream_t st) {
+                                const Coarse* co, hipStream_t st) {
     GatherArgs A{};
     fill_gather_common(A, P, W);
     A.ctl = W.ctl;
     fill_round(A, W, rr);
-    return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, GM_REVEAL, P, P.N, st)
-                           : gather_by_d<f32_tag>(A, GM_REVEAL, P, P.N, st);
+    return gather_any(A, GM_REVEAL, P, P.N, co, st);
 }
 
 hipError_t launch_gather_cells(const Problem& P, const Work& W, const RevealRound& rr,
-                               hipStream_t st) {
+                               const Coarse* co, hipStream_t st) {
     if (W.cache_cap <= 0) return hipSuccess;
     GatherArgs A{};
     fill_gather_common(A, P, W);
     A.ctl = W.ctl;
     fill_round(A, W, rr);
-    return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, GM_CELLS, P, W.cache_cap, st)
-                           : gather_by_d<f32_tag>(A, GM_CELLS, P, W.cache_cap, st);
+    return gather_any(A, GM_CELLS, P, W.cache_cap, co, st);
 }
 
 hipError_t launch_gather_score(const Problem& P, const Work& W, bool use_ctl, float* out,
-                               float* cells, hipStream_t st) {
+                               float* cells, bool score_slots, hipStream_t st) {
     GatherArgs A{};
     fill_gather_common(A, P, W);
     A.ctl = use_ctl ? W.ctl : nullptr;
     A.out = out;
     A.cells = cells;
-    return P.dt == DT_BF16 ? gather_by_d<bf16_tag>(A, GM_SCORE, P, P.N, st)
-                           : gather_by_d<f32_tag>(A, GM_SCORE, P, P.N, st);
+    A.score_slots = score_slots ? 1 : 0;
+    return gather_any(A, GM_SCORE, P, P.N, nullptr, st);
 }
 
 // Exact scores of cached survivors: the T cells of a slot are laid out as the column

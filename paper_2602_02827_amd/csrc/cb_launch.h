@@ -37,6 +37,19 @@ struct Work {
     int32_t* cid;         // [nq][cache_cap] document id of a slot
     float2* cstat;        // [nq][cache_cap] revealed sum / centred squares of a slot
     float* ccell;         // [nq][cache_cap][TP] the slot's MaxSim cells
+    // coarse pass: int8 codes of the queries, written per call
+    int8_t* q8;           // [nq][T][d]
+    float* qscale;        // [nq]
+    void* qscratch;       // quantize_scratch_bytes(nq)
+};
+
+// int8 codes for the coarse elimination pass (implementation appendix, quantized layout):
+// a code c decodes to c * scale.  All device pointers.
+struct Coarse {
+    const int8_t* docs8;  // [total][d] codes of the document tokens
+    const float* dscale;  // [1] their decode scale
+    int8_t* Q8;           // [nq][T][d] codes of the queries (written by the call)
+    float* qscale;        // [nq] decode scale of each query
 };
 
 struct Trace {            // all null when tracing is off
@@ -68,32 +81,37 @@ hipError_t launch_init(const Problem& P, const Work& W, const Knobs& kn, int R, 
 
 // Reveal one batch for every active (query, doc) pair by gathering the documents.
 hipError_t launch_gather_reveal(const Problem& P, const Work& W, const RevealRound& rr,
-                                hipStream_t st);
+                                const Coarse* co, hipStream_t st);
 
 // The reveal of round rr for queries that fit the cell cache: all T cells of every active
 // document are computed once and cached; later rounds and the rescore read them back.
 hipError_t launch_gather_cells(const Problem& P, const Work& W, const RevealRound& rr,
-                               hipStream_t st);
+                               const Coarse* co, hipStream_t st);
 hipError_t launch_cached_score(const Problem& P, const Work& W, float* out, hipStream_t st);
 
-// Exact scores.  ctl == nullptr: all documents of every query, written by doc id into
-// `out` ([nq][N]); otherwise the current active set, written by list position.
+// Exact scores from the stored embeddings.  ctl == nullptr: all documents of every query,
+// written by doc id into `out` ([nq][N]); otherwise the current active set, written by list
+// position (score_slots: including the queries whose list holds cache slots, whose cached
+// cells are coarse and cannot give the exact score).
 hipError_t launch_gather_score(const Problem& P, const Work& W, bool use_ctl, float* out,
-                               float* cells, hipStream_t st);
+                               float* cells, bool score_slots, hipStream_t st);
 
 // Dense (corpus-streaming) kernel for bf16: Full-MaxSim scores or the first reveal batch.
 hipError_t launch_dense_prepare(const Problem& P, const Work& W, int chunk_tokens, int* n_chunks,
                                 hipStream_t st);
+// co != nullptr: the pass runs on the int8 codes (integer matrix instructions, exact int32
+// maxima decoded by the two scales) instead of the stored embeddings.
 hipError_t launch_dense_score(const Problem& P, const Work& W, int chunk_tokens, int n_chunks,
-                              float* out, float* cells, hipStream_t st);
+                              float* out, float* cells, const Coarse* co, hipStream_t st);
 hipError_t launch_dense_reveal(const Problem& P, const Work& W, int chunk_tokens, int n_chunks,
-                               const RevealRound& rr, int G, hipStream_t st);
+                               const RevealRound& rr, int G, const Coarse* co, hipStream_t st);
 // The same pass for a round >= 2: runs only if the round's device-side test picks it, writes the
 // batch statistics of every (active ids-mode query, document) to stat2; k_select_prune merges
 // them into the running statistics of the documents still active.
 hipError_t launch_dense_reveal_later(const Problem& P, const Work& W, int chunk_tokens,
-                                     int n_chunks, const RevealRound& rr, int G, hipStream_t st);
-bool dense_supported(const Problem& P);
+                                     int n_chunks, const RevealRound& rr, int G, const Coarse* co,
+                                     hipStream_t st);
+bool dense_supported(const Problem& P, const Coarse* co);
 
 hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
                                const RevealRound& rr, const Trace& tr, hipStream_t st);
@@ -102,6 +120,14 @@ hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
 // list position); else all N documents (vals indexed by id).
 hipError_t launch_topk(const Problem& P, const Work& W, bool use_ctl, const float* vals, int K,
                        int64_t* out_ids, float* out_scores, hipStream_t st);
+
+// int8 codes of x ([n_segments][seg_elems] values of dtype dt): per segment, clip = the
+// nearest-rank permille/1000 percentile of |x|, code = rint(x * 127 / clip) saturated to
+// +-127, scales[seg] = clip / 127.  scratch: quantize_scratch_bytes(n_segments).
+size_t quantize_scratch_bytes(int64_t n_segments);
+hipError_t launch_quantize_i8(const void* x, int dt, int64_t n_segments, int64_t seg_elems,
+                              int permille, int8_t* codes, float* scales, void* scratch,
+                              hipStream_t st);
 
 hipError_t launch_validate_offsets(const int64_t* off, int64_t N, int64_t total, int* flag,
                                    hipStream_t st);

@@ -1,0 +1,163 @@
+// int8 codes for the coarse elimination pass (paper, implementation appendix,
+// "Cache-separated quantized layout": clip to the 99.9th percentile of the absolute values,
+// then linear quantisation to int8).
+//
+// Reading of the paper fixed here: the percentile is the nearest-rank one -- the element of
+// rank ceil(n * permille / 1000) of the ascending order of |x| over one segment (the whole
+// corpus matrix, or one query's T x d matrix) -- found exactly by a radix select on the bit
+// pattern of |x| (for non-negative floats the bit pattern orders like the value).  A code is
+// rint(x * (127 / clip)) saturated to [-127, 127], all in single precision, and decodes to
+// code * (clip / 127).
+//
+// Everything stays on the device: three histogram passes (11 + 11 + 10 bits; bf16 inputs need
+// only the first two) each followed by a one-wavefront kernel that picks the bin holding the
+// rank, then the quantising pass.  Segments are independent (grid.y).
+#include "cb_launch.h"
+
+namespace cb {
+
+constexpr int QH_BINS = 2048;
+constexpr int QH_THREADS = 256;
+
+struct SelState {                 // per segment, in the workspace
+    unsigned long long rank;      // remaining 1-based ascending rank inside the current prefix
+    uint32_t prefix, mask;        // key bits fixed so far
+    uint32_t pad[2];
+};
+
+template <bool BF16>
+__device__ __forceinline__ uint32_t abs_key(const void* x, int64_t i) {
+    if (BF16) return ((uint32_t)(((const uint16_t*)x)[i] & 0x7fffu)) << 16;
+    return ((const uint32_t*)x)[i] & 0x7fffffffu;
+}
+
+__global__ void k_quant_init(SelState* st, unsigned long long* hist, int64_t nseg,
+                             unsigned long long rank) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nseg) {
+        SelState s;
+        s.rank = rank;
+        s.prefix = 0;
+        s.mask = 0;
+        s.pad[0] = s.pad[1] = 0;
+        st[i] = s;
+    }
+    if (i < nseg * QH_BINS) hist[i] = 0ull;
+}
+
+// histogram of the `shift`-ed digit over the keys that match the segment's prefix
+template <bool BF16>
+__global__ __launch_bounds__(QH_THREADS) void k_quant_hist(const void* x, int64_t seg_elems,
+                                                           const SelState* st,
+                                                           unsigned long long* hist, int shift,
+                                                           int nbins) {
+    __shared__ uint32_t lh[QH_BINS];
+    const int64_t seg = blockIdx.y;
+    for (int i = threadIdx.x; i < QH_BINS; i += QH_THREADS) lh[i] = 0;
+    __syncthreads();
+    const uint32_t prefix = st[seg].prefix, mask = st[seg].mask;
+    const int64_t base = seg * seg_elems;
+    // a block's share stays below 2^32 elements (the launch gives every block <= 2^24)
+    for (int64_t i = (int64_t)blockIdx.x * QH_THREADS + threadIdx.x; i < seg_elems;
+         i += (int64_t)gridDim.x * QH_THREADS) {
+        const uint32_t k = abs_key<BF16>(x, base + i);
+        if ((k & mask) == prefix) atomicAdd(&lh[(k >> shift) & (nbins - 1)], 1u);
+    }
+    __syncthreads();
+    unsigned long long* gh = hist + seg * QH_BINS;
+    for (int i = threadIdx.x; i < nbins; i += QH_THREADS)
+        if (lh[i]) atomicAdd(&gh[i], (unsigned long long)lh[i]);
+}
+
+// one wavefront per segment: ascending walk to the bin that holds the rank; clears the bins
+__global__ __launch_bounds__(64) void k_quant_pick(SelState* st, unsigned long long* hist,
+                                                   int shift, int nbins) {
+    const int64_t seg = blockIdx.x;
+    unsigned long long* gh = hist + seg * QH_BINS;
+    const int lane = threadIdx.x;
+    const int per = nbins / 64;
+    const unsigned long long rank = st[seg].rank;
+    unsigned long long local = 0;
+    for (int j = 0; j < per; ++j) local += gh[lane * per + j];
+    unsigned long long incl = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned long long t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+    }
+    const unsigned long long excl = incl - local;
+    if (excl < rank && rank <= incl) {
+        unsigned long long run = excl;
+        for (int j = 0; j < per; ++j) {
+            const unsigned long long c = gh[lane * per + j];
+            if (run + c >= rank) {
+                SelState s = st[seg];
+                s.prefix |= (uint32_t)(lane * per + j) << shift;
+                s.mask |= (uint32_t)(nbins - 1) << shift;
+                s.rank = rank - run;
+                st[seg] = s;
+                break;
+            }
+            run += c;
+        }
+    }
+    __syncthreads();
+    for (int i = lane; i < QH_BINS; i += 64) gh[i] = 0ull;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(QH_THREADS) void k_quant_codes(const void* x, int64_t seg_elems,
+                                                            const SelState* st, int8_t* out,
+                                                            float* scales) {
+    const int64_t seg = blockIdx.y;
+    const float clip = __uint_as_float(st[seg].prefix);
+    const float inv = clip > 0.f ? 127.0f / clip : 0.f;
+    if (blockIdx.x == 0 && threadIdx.x == 0) scales[seg] = clip / 127.0f;
+    const int64_t base = seg * seg_elems;
+    for (int64_t i = (int64_t)blockIdx.x * QH_THREADS + threadIdx.x; i < seg_elems;
+         i += (int64_t)gridDim.x * QH_THREADS) {
+        float v;
+        if (BF16) v = __uint_as_float((uint32_t)((const uint16_t*)x)[base + i] << 16);
+        else v = ((const float*)x)[base + i];
+        float r = rintf(v * inv);
+        r = r > 127.f ? 127.f : (r < -127.f ? -127.f : r);
+        out[base + i] = (int8_t)r;
+    }
+}
+
+size_t quantize_scratch_bytes(int64_t n_segments) {
+    return (size_t)n_segments * (sizeof(SelState) + sizeof(unsigned long long) * QH_BINS);
+}
+
+// x: [n_segments][seg_elems] of dt; codes: same shape; scales: [n_segments].
+hipError_t launch_quantize_i8(const void* x, int dt, int64_t n_segments, int64_t seg_elems,
+                              int permille, int8_t* codes, float* scales, void* scratch,
+                              hipStream_t st) {
+    SelState* state = (SelState*)scratch;
+    unsigned long long* hist = (unsigned long long*)(state + n_segments);
+    // ceil(seg_elems * permille / 1000), exact in 64-bit integers
+    const unsigned long long rank =
+        ((unsigned long long)seg_elems * (unsigned long long)permille + 999ull) / 1000ull;
+    const int64_t init_n = n_segments * QH_BINS;
+    k_quant_init<<<(unsigned)((init_n + 255) / 256), 256, 0, st>>>(state, hist, n_segments,
+                                                                  rank < 1 ? 1 : rank);
+    int64_t bx = (seg_elems + (int64_t)QH_THREADS * 64 - 1) / ((int64_t)QH_THREADS * 64);
+    if (bx > 8192) bx = 8192;
+    if (bx < 1) bx = 1;
+    while (seg_elems / bx > (1ll << 24) * QH_THREADS) bx *= 2;   // per-block counts fit 32 bits
+    const dim3 grid((unsigned)bx, (unsigned)n_segments);
+    const bool bf = dt == DT_BF16;
+    const int npass = bf ? 2 : 3;
+    for (int p = 0; p < npass; ++p) {
+        const int shift = p == 0 ? 21 : (p == 1 ? 10 : 0);
+        const int nbins = p == 2 ? 1024 : 2048;
+        if (bf) k_quant_hist<true><<<grid, QH_THREADS, 0, st>>>(x, seg_elems, state, hist, shift, nbins);
+        else k_quant_hist<false><<<grid, QH_THREADS, 0, st>>>(x, seg_elems, state, hist, shift, nbins);
+        k_quant_pick<<<(unsigned)n_segments, 64, 0, st>>>(state, hist, shift, nbins);
+    }
+    if (bf) k_quant_codes<true><<<grid, QH_THREADS, 0, st>>>(x, seg_elems, state, codes, scales);
+    else k_quant_codes<false><<<grid, QH_THREADS, 0, st>>>(x, seg_elems, state, codes, scales);
+    return hipGetLastError();
+}
+
+}  // namespace cb

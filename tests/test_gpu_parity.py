@@ -139,11 +139,15 @@ def test_mid_text_config2_scaled(B, S, oracle_mod):
 
 
 # ------------------------------------------------------------------ Col-Bandit
-def _compare_rounds(oracle_mod, tr, q, Hq, K, M, Bsz, alpha, delta, pi, a=-1.0, b=1.0):
+def _compare_rounds(oracle_mod, tr, q, Hq, K, M, Bsz, alpha, delta, pi, a=-1.0, b=1.0, Hexact=None):
     """Oracle on the GPU's cells vs the GPU trace.  Returns the round of first divergence
-    (band documents only) or None."""
+    (band documents only) or None.  Hexact: the rounds decide on Hq (coarse cells) and the
+    rescore reads Hexact."""
     N, T = Hq.shape
-    orc = oracle_mod.colbandit_from_H(Hq, K, M, Bsz, alpha, delta, pi, a, b)
+    if Hexact is None:
+        orc = oracle_mod.colbandit_from_H(Hq, K, M, Bsz, alpha, delta, pi, a, b)
+    else:
+        orc = oracle_mod.colbandit_coarse(Hq, Hexact, K, M, Bsz, alpha, delta, pi, a, b)
     for r in range(orc.rounds):
         assert tr.count[r, q] == orc.counts[r], (q, r)
         live = ~np.isnan(orc.lcb[r])
@@ -161,10 +165,18 @@ def _compare_rounds(oracle_mod, tr, q, Hq, K, M, Bsz, alpha, delta, pi, a=-1.0, 
 
 
 def _run_colbandit_case(B, oracle_mod, w, K, M, Bsz, alpha, delta=0.01, seed=0, a=0.0, b=0.0,
-                        force_gather=False, max_diverged=0.15, later_rounds=0):
+                        force_gather=False, max_diverged=0.15, later_rounds=0, coarse=None, **kw):
+    """coarse = (docs_i8, docs_scale): the rounds run on int8 codes; the oracle then decides on
+    the GPU's coarse cells and rescored from its exact ones."""
     full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=0, want_cells=True)
+    ckw = {} if coarse is None else {"docs_i8": coarse[0], "docs_scale": coarse[1]}
     res = B.colbandit_topk(w.Q, w.docs, w.offsets, K, alpha, delta, M, seed, B=Bsz, a=a, b=b,
-                           trace=True, force_gather=force_gather, later_rounds=later_rounds)
+                           trace=True, force_gather=force_gather, later_rounds=later_rounds, **ckw, **kw)
+    Hc = None
+    if coarse is not None:
+        cm = B.colbandit_coarse_maxsim(w.Q, coarse[0], coarse[1], w.offsets, want_cells=True)
+        torch.cuda.synchronize()
+        Hc = cm["cells"].cpu().numpy().astype(np.float64)
     torch.cuda.synchronize()
     H = full["cells"].cpu().numpy().astype(np.float64)
     Sfull = full["scores"].cpu().numpy()
@@ -176,7 +188,11 @@ def _run_colbandit_case(B, oracle_mod, w, K, M, Bsz, alpha, delta=0.01, seed=0, 
     for q in range(w.nq):
         pi = B.colbandit_permutation(seed, q, w.T)
         np.testing.assert_array_equal(pi, oracle_mod.permutation(seed, q, w.T))
-        div, orc = _compare_rounds(oracle_mod, tr, q, H[q], K, M, Bsz, alpha, delta, pi, aa, bb)
+        if Hc is None:
+            div, orc = _compare_rounds(oracle_mod, tr, q, H[q], K, M, Bsz, alpha, delta, pi, aa, bb)
+        else:
+            div, orc = _compare_rounds(oracle_mod, tr, q, Hc[q], K, M, Bsz, alpha, delta, pi, aa, bb,
+                                       Hexact=H[q])
         st = res["stats"][q]
         # survivor scores carry the same bits as the exhaustive path
         ok = ids[q] >= 0
@@ -402,6 +418,97 @@ def test_validate_offsets(B, S):
     # a bad table must not fault: rows are clamped, results are merely meaningless
     B.colbandit_full_maxsim(w.Q, w.docs, bad, K=0)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ int8 coarse elimination pass
+def _host_values(x):
+    return x.float().cpu().numpy()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("rows,d,nseg,permille", [(3001, 128, 1, 999), (64, 128, 4, 999), (32 * 9, 64, 9, 999),
+                                                   (1, 128, 1, 999), (500, 128, 1, 1000), (500, 128, 5, 500)])
+def test_quantize_i8_codes_and_scales_match_oracle(B, oracle_mod, dtype, rows, d, nseg, permille):
+    """Percentile clip and codes are integer results: exact equality with the oracle, which
+    takes the deciding arithmetic in single precision as well."""
+    g = torch.Generator(device="cpu"); g.manual_seed(rows * 7 + d + nseg)
+    x = torch.randn((rows, d), generator=g) * 0.09
+    x[0, 0] = 3.0                                   # an outlier far above the clip
+    x = x.to(torch.bfloat16 if dtype == "bf16" else torch.float32).cuda()
+    codes, scales = B.colbandit_quantize_i8(x, n_segments=nseg, permille=permille)
+    torch.cuda.synchronize()
+    xs = _host_values(x).reshape(nseg, -1)
+    for sidx in range(nseg):
+        clip = oracle_mod.abs_percentile(xs[sidx], permille)
+        assert scales[sidx].item() == np.float32(clip) / np.float32(127.0)
+        want = oracle_mod.quantize_i8(xs[sidx], clip)
+        np.testing.assert_array_equal(codes.cpu().numpy().reshape(nseg, -1)[sidx], want)
+    if permille == 999 and rows * d // nseg >= 2000:
+        assert codes.abs().max().item() == 127       # the outlier saturates
+    z = torch.zeros((4, d), dtype=x.dtype, device="cuda")
+    cz, sz = B.colbandit_quantize_i8(z)
+    assert int(cz.abs().max()) == 0 and float(sz[0]) == 0.0
+
+
+@pytest.mark.parametrize("nq,T,d", [(1, 32, 128), (5, 32, 128), (20, 24, 128), (3, 40, 128), (2, 100, 128),
+                                    (4, 32, 64), (70, 16, 64)])
+def test_coarse_maxsim_cells_are_the_integer_maxima(B, S, oracle_mod, nq, T, d):
+    """Cells from int8 codes: the integer dot products and their maxima are exact, so the
+    decoded cell must equal float(int) * (sq * sd) bit for bit."""
+    lengths = [1, 2, 15, 16, 17, 31, 33, 63, 64, 65, 100, 255, 257, 1030] + \
+        np.random.default_rng(d + T).integers(1, 200, 150).tolist()
+    w = _custom(S, lengths, nq, T, d, "bf16", 11 + nq)
+    d8, ds = B.colbandit_quantize_i8(w.docs)
+    cm = B.colbandit_coarse_maxsim(w.Q, d8, ds, w.offsets, want_cells=True)
+    torch.cuda.synchronize()
+    q8 = cm["q_codes"].cpu().numpy()
+    qs = cm["q_scales"].cpu().numpy()
+    Qh = w.host_queries()
+    off = w.offsets.cpu().numpy()
+    D8 = d8.cpu().numpy()
+    sd = np.float32(ds.cpu().numpy()[0])
+    cells = cm["cells"].cpu().numpy()
+    for q in range(nq):
+        # the call's own query codes follow the same scheme
+        clip = oracle_mod.abs_percentile(Qh[q], 999)
+        assert qs[q] == np.float32(clip) / np.float32(127.0)
+        np.testing.assert_array_equal(q8[q], oracle_mod.quantize_i8(Qh[q], clip))
+        if q < 6:
+            _, Hint = oracle_mod.maxsim_cells_i8(q8[q], qs[q], D8, sd, off)
+            want = Hint.astype(np.float32) * (np.float32(qs[q]) * sd)
+            np.testing.assert_array_equal(cells[q], want)
+    # row sums in the kernels' fixed order vs a plain sum
+    np.testing.assert_allclose(cm["scores"].cpu().numpy(), cells.sum(axis=2), rtol=1e-5, atol=1e-5)
+
+
+@pytest.mark.parametrize("alpha,K,M,Bsz", [(0.2, 5, 5, 4), (1.0, 5, 5, 4), (0.5, 10, 5, 3), (0.2, 5, 0, 16)])
+def test_colbandit_on_int8_codes_rounds_match_oracle(B, S, oracle_mod, alpha, K, M, Bsz):
+    """Rounds decided on coarse cells, survivors rescored exactly (implementation appendix):
+    every bound, threshold and survivor against the oracle's coarse-elimination mode, and the
+    returned scores carry the exhaustive path's bits."""
+    w = S.config(1, device="cuda", scale=0.04, nq=6)            # N=2000, planted docs
+    d8, ds = B.colbandit_quantize_i8(w.docs)
+    _run_colbandit_case(B, oracle_mod, w, K, M, Bsz, alpha, coarse=(d8, ds))
+    w = S.config(3, device="cuda", scale=0.005, nq=4)           # 100 pages x 1030 tokens, T=24
+    d8, ds = B.colbandit_quantize_i8(w.docs)
+    _run_colbandit_case(B, oracle_mod, w, K, M, Bsz, alpha, coarse=(d8, ds))
+
+
+def test_colbandit_on_int8_codes_all_reveal_paths_agree(B, S, oracle_mod):
+    rng = np.random.default_rng(3)
+    w = _custom(S, rng.integers(1, 120, 2500).tolist(), 5, 32, 128, "bf16", 23)
+    d8, ds = B.colbandit_quantize_i8(w.docs)
+    kw = dict(docs_i8=d8, docs_scale=ds, trace=True)
+    base = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.5, 0.01, 5, 3, **kw)
+    for extra in (dict(force_gather=True), dict(no_cell_cache=True), dict(later_rounds=1),
+                  dict(later_rounds=2), dict(later_rounds=1, no_cell_cache=True)):
+        other = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.5, 0.01, 5, 3, **kw, **extra)
+        torch.cuda.synchronize()
+        _same_run(base, other)
+    # fp32 embeddings with int8 codes: the rounds use the codes, the rescore the fp32 gather
+    w32 = _custom(S, rng.integers(1, 60, 600).tolist(), 2, 32, 128, "f32", 29)
+    d8, ds = B.colbandit_quantize_i8(w32.docs)
+    _run_colbandit_case(B, oracle_mod, w32, 5, 5, 4, 0.3, coarse=(d8, ds))
 
 
 # ------------------------------------------------------------------ full size, bench launch configuration
