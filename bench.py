@@ -198,6 +198,21 @@ def main():
                         "(kernel + chunk table + top-K, %.3f ms) runs at %.1f TFLOP/s"
                         % (ms_full, tflops)}
 
+    # the gathered rounds (rounds >= 2) against the HBM roofline: every document that survives
+    # round 1 is streamed once (visit-once cell cache), so the algorithmic bytes are the
+    # survivors' tokens; their mean length is taken as the corpus mean (the exact ids stay on
+    # the device)
+    pairs2 = float(sum(s["survivors"][1] for s in st if s["rounds"] >= 2))
+    gather_bytes = pairs2 * (total / float(N)) * d * 2
+    ms_later = st[0]["ms_later_reveals"]
+    gather = {"bound": "hbm", "kernel": "k_gather (rounds >= 2, visit-once cell cache)",
+              "achieved": round(gather_bytes / (ms_later * 1e-3) / 1e9, 1) if ms_later > 0 else None,
+              "peak": PEAK_HBM_GBS, "unit": "GB/s",
+              "frac": round(gather_bytes / (ms_later * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if ms_later > 0 else None,
+              "pairs": pairs2, "ms": round(ms_later, 3),
+              "note": "bytes = (query, document) pairs entering round 2 x mean document bytes; "
+                      "ms = all reveal launches of rounds >= 2 (events, statistics call)"}
+
     line = {
         "metric": "queries/s through one step = Full-MaxSim top-K + Col-Bandit top-K at N=%d,T=%d,"
                   "d=%d,K=%d (MaxSim cells/s and Overlap@%d vs exhaustive in full_maxsim / "
@@ -226,6 +241,7 @@ def main():
                       "survivor_scores_bit_identical_to_full": same_bits},
         "colbandit_int8": int8,
         "roofline": roofline,
+        "roofline_gather": gather,
         "paper_context": "paper (CPU, real embeddings): up to ~8x fewer MaxSim FLOPs, up to ~13x "
                          "single-thread CPU speedup at Overlap@5 >= 0.9; no GPU kernel reported",
         "setup_s": round(gen_s, 1),
