@@ -17,7 +17,7 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 constexpr int kChunkTokens = 4096;
 
 struct Layout {
-    size_t ctl, list0, list1, stat, stat2, pairs, rescored, scores, cnt_hist, tau_hist, pi,
+    size_t ctl, list0, list1, stat, stat2, pairs, seg_cnt, rescored, scores, cnt_hist, tau_hist, pi,
         chunk_doc, flag, cid, cstat, ccell, q8, qscale, qscratch, total;
     int cache_cap, TP;
 };
@@ -40,6 +40,7 @@ Layout make_layout(int nq, int T, int d, int64_t N, int64_t total_tokens) {
     L.stat = take(8 * qn);
     L.stat2 = take(8 * qn);
     L.pairs = take(8 * (size_t)(COLBANDIT_MAX_ROUNDS + 4));
+    L.seg_cnt = take(4 * (size_t)nq * 64);
     L.rescored = take(4 * qn);
     L.scores = take(4 * qn);
     L.cnt_hist = take(4 * (size_t)(COLBANDIT_MAX_ROUNDS + 2) * nq);
@@ -71,6 +72,7 @@ Work carve(void* ws, const Layout& L) {
     W.stat = (float2*)(b + L.stat);
     W.stat2 = (float2*)(b + L.stat2);
     W.pairs = (unsigned long long*)(b + L.pairs);
+    W.seg_cnt = (int32_t*)(b + L.seg_cnt);
     W.rescored = (float*)(b + L.rescored);
     W.scores = (float*)(b + L.scores);
     W.cnt_hist = (int32_t*)(b + L.cnt_hist);

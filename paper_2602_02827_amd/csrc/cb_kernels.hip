@@ -468,6 +468,23 @@ __device__ __forceinline__ int block_excl_scan(int v, int* wtot, int& total) {
     return base + incl - v;
 }
 
+// hist[bin] += 1 for every lane with `on`.  Keys of similar magnitude share their leading
+// digit, so plain LDS atomics of a wavefront would pile onto one address: up to four rounds of
+// "first pending lane's bin, one add for all lanes that share it" come first, the rest (spread
+// digits) go as ordinary atomics.
+__device__ __forceinline__ void hist_add(uint32_t* hist, int bin, bool on) {
+    unsigned long long pending = __ballot(on);
+#pragma unroll 1
+    for (int it = 0; it < 4 && pending != 0ull; ++it) {
+        const int leader = __ffsll((long long)pending) - 1;
+        const int lbin = __shfl(bin, leader);
+        const unsigned long long same = __ballot(on && bin == lbin) & pending;
+        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[lbin], (uint32_t)__popcll(same));
+        pending &= ~same;
+    }
+    if ((pending >> (threadIdx.x & 63)) & 1ull) atomicAdd(&hist[bin], 1u);
+}
+
 // Key of the K-th largest element (1 <= K <= count) of key_of(0..count-1): three radix
 // passes (11+11+10 bits) over the candidates with an LDS histogram each.  Each thread
 // takes SEL_ITEMS strided entries per trip so that several loads are in flight.
@@ -496,10 +513,69 @@ __device__ uint32_t block_kth_largest(int count, int K, KeyFn key_of, uint32_t* 
 #pragma unroll
             for (int u = 0; u < SEL_ITEMS; ++u) {
                 const int idx = base + u * SEL_THREADS + threadIdx.x;
-                if (idx < count && (key[u] & pmask) == prefix)
-                    atomicAdd(&hist[(key[u] >> shift) & (nbins - 1)], 1u);
+                hist_add(hist, (int)((key[u] >> shift) & (nbins - 1)),
+                         idx < count && (key[u] & pmask) == prefix);
             }
         }
+        __syncthreads();
+        if (threadIdx.x < 64) {
+            const int lane = threadIdx.x;
+            const int per = nbins / 64;
+            const int hi = nbins - 1 - lane * per;       // this lane's bins, descending
+            int local = 0;
+            for (int j = 0; j < per; ++j) local += (int)hist[hi - j];
+            int incl = local;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o);
+                if (lane >= o) incl += t;
+            }
+            const int excl = incl - local;
+            if (excl < kk && kk <= incl) {
+                int run = excl;
+                for (int j = 0; j < per; ++j) {
+                    const int c = (int)hist[hi - j];
+                    if (run + c >= kk) {
+                        pick[0] = hi - j;
+                        pick[1] = kk - run;
+                        break;
+                    }
+                    run += c;
+                }
+            }
+        }
+        __syncthreads();
+        prefix |= (uint32_t)pick[0] << shift;
+        pmask |= (uint32_t)(nbins - 1) << shift;
+        kk = pick[1];
+        __syncthreads();
+    }
+    return prefix;
+}
+
+// The same selection over SEL_SAMPLE keys that each thread computes once and keeps in
+// registers for all three passes (thread t holds keys t, t + SEL_THREADS, ...).
+constexpr int SEL_SAMPLE_PER_THREAD = SEL_SAMPLE / SEL_THREADS;
+template <class KeyFn>
+__device__ uint32_t block_kth_largest_sample(int K, KeyFn key_of, uint32_t* hist, int* pick) {
+    uint32_t key[SEL_SAMPLE_PER_THREAD];
+#pragma unroll
+    for (int u = 0; u < SEL_SAMPLE_PER_THREAD; ++u) key[u] = key_of(u * SEL_THREADS + (int)threadIdx.x);
+    uint32_t prefix = 0, pmask = 0;
+    int kk = K;
+#pragma unroll 1
+    for (int p = 0; p < 3; ++p) {
+        const int shift = p == 0 ? 21 : (p == 1 ? 10 : 0);
+        const int nbins = p == 2 ? 1024 : 2048;
+        for (int i = threadIdx.x; i < 2048; i += SEL_THREADS) hist[i] = 0;
+        if (threadIdx.x == 0) {
+            pick[0] = 0;
+            pick[1] = 1;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < SEL_SAMPLE_PER_THREAD; ++u)
+            hist_add(hist, (int)((key[u] >> shift) & (nbins - 1)), (key[u] & pmask) == prefix);
         __syncthreads();
         if (threadIdx.x < 64) {
             const int lane = threadIdx.x;
@@ -602,7 +678,41 @@ struct SelArgs {
     float* tr_lcb;
     float* tr_ucb;
     uint8_t* tr_alive;
+    // segmented pre-filter of long lists (k_select_segments): candidates of segment s sit at
+    // out[s * seg_len(count, n_seg) ...], seg_cnt[q][s] of them
+    int n_seg;                // 0: no segmented pre-filter ran
+    int32_t* seg_cnt;         // [nq][SEG_MAX]
 };
+
+constexpr int SEG_MAX = 64;
+// entries per segment: a multiple of the widest per-thread run
+__device__ __host__ __forceinline__ int seg_len(int count, int n_seg) {
+    return ((count + n_seg - 1) / n_seg + 15) & ~15;
+}
+
+// Candidates that the segment workgroups left at the segment starts of `buf` -> one contiguous
+// run at the front, order kept.  A destination never lies beyond its source, and a chunk is read
+// completely before it is written.
+__device__ int merge_segments(int32_t* buf, const int32_t* cnt, int count, int n_seg) {
+    const int len = seg_len(count, n_seg);
+    int base = 0;
+    for (int sg = 0; sg < n_seg; ++sg) {
+        const int c = cnt[sg];
+        const int src = sg * len;
+        if (src != base) {
+            for (int k0 = 0; k0 < c; k0 += SEL_THREADS) {
+                const int k = k0 + (int)threadIdx.x;
+                const int v = k < c ? buf[src + k] : 0;
+                __syncthreads();
+                if (k < c) buf[base + k] = v;
+                __syncthreads();
+            }
+        }
+        base += c;
+    }
+    __syncthreads();
+    return base;
+}
 
 __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
     __shared__ uint32_t hist[2048];
@@ -647,7 +757,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
         __syncthreads();
     }
 
-    if (dense && c.mode == 0 && in) {   // fold in the batch a dense pass left in stat2
+    const bool segmented = A.n_seg > 0 && count > SEL_PREFILTER_MIN && !slots;
+    if (dense && c.mode == 0 && in && !segmented) {   // fold in the batch a dense pass left in stat2
         float2* dst = A.stat + (size_t)q * A.N;
         const float2* bat = A.stat2 + (size_t)q * A.N;
         for (int idx = threadIdx.x; idx < count; idx += SEL_THREADS) {
@@ -744,9 +855,25 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
     // those few.
     const int32_t* sel_in = in;
     int sel_count = count;
-    if (count > SEL_PREFILTER_MIN) {
+    if (segmented) {
+        // the segment workgroups have folded, sampled and pre-filtered; gather their candidates
+        sel_count = merge_segments(out, A.seg_cnt + (size_t)q * SEG_MAX, count, A.n_seg);
+        sel_in = out;
+        if (dense && c.mode == 0 && in) {       // the candidates' statistics take the round's batch
+            float2* dst = A.stat + (size_t)q * A.N;
+            const float2* bat = A.stat2 + (size_t)q * A.N;
+            for (int idx = threadIdx.x; idx < sel_count; idx += SEL_THREADS) {
+                const int e = out[idx];
+                float2 st = dst[e];
+                const float2 bb = bat[e];
+                merge_stats(st.x, st.y, A.n_prev, bb.x, bb.y, A.nb);
+                dst[e] = st;
+            }
+            __syncthreads();
+        }
+    } else if (count > SEL_PREFILTER_MIN) {
         auto key_s = [&](int j) -> uint32_t { return key_of(in, sample_pos(j, count)); };
-        const float tau_lo = key_float(block_kth_largest(SEL_SAMPLE, A.K, key_s, hist, pick));
+        const float tau_lo = key_float(block_kth_largest_sample(A.K, key_s, hist, pick));
         // the streaming pass: wide chunks keep enough loads in flight for one workgroup
         sel_count = filter(std::integral_constant<int, SEL_ITEMS_WIDE>{}, in, count, out, tau_lo, false);
         sel_in = out;
@@ -774,6 +901,160 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
             A.tr_tau[(A.r - 1) * A.nq + q] = tau;
         }
     }
+}
+
+// A cheap upper estimate of interval()'s UCB for the pre-filter (n, T, kappa, b uniform).
+struct FastUcb {
+    float c_hat, c_sig, rest_b;
+    int mode;           // 0: hard bound only (n <= 1), 1: hybrid, 2: exact sum (n >= T)
+};
+__device__ __forceinline__ FastUcb fast_ucb_consts(int n, int T, float kappa, float b) {
+    FastUcb f;
+    f.mode = n <= 1 ? 0 : (n >= T ? 2 : 1);
+    f.c_hat = n > 0 ? (float)T / (float)n : 0.f;
+    f.c_sig = n > 1 ? kappa * kappa / (float)(n - 1) : 0.f;
+    f.rest_b = (float)(T - n) * b;
+    return f;
+}
+__device__ __forceinline__ float fast_ucb(float S, float M2, int n, int T, const FastUcb& f) {
+    (void)n; (void)T;
+    const float ub = S + f.rest_b;
+    if (f.mode == 0) return ub;
+    if (f.mode == 2) return S;
+    const float r = __builtin_amdgcn_sqrtf(fmaxf(M2, 0.f) * f.c_sig);
+    return fminf(ub, S * f.c_hat + r);
+}
+
+// Pre-filter of a long active list, spread over n_seg workgroups per query (one workgroup cannot
+// pull a multi-megabyte list from memory fast enough).  Every workgroup of a query derives the
+// same lower threshold tau_lo from the same sample, then streams its own segment once and keeps
+// {UCB >= tau_lo} in order at the start of its segment of the output list, recording how many.
+// In a corpus-pass round the round's batch (stat2) is merged in registers only: nothing is
+// written back here, because other workgroups of the query are still sampling; k_select_prune
+// gathers the segments and stores the merged statistics of the candidates, the only entries
+// that are ever read again.
+__global__ __launch_bounds__(SEL_THREADS) void k_select_segments(SelArgs A) {
+    __shared__ uint32_t hist[2048];
+    __shared__ int pick[2];
+    __shared__ int wtot[SEL_WAVES];
+    const int q = blockIdx.y, sg = blockIdx.x;
+    const QueryCtl c = A.ctl[q];
+    if (!c.active) return;
+    const int count = c.count;
+    if (count <= SEL_PREFILTER_MIN) return;
+    const bool dense = A.dense_thr != ~0ull && dense_round(A.pairs + A.r, A.dense_thr);
+    const bool slots = c.mode == 1 || (c.mode == 0 && !c.implicit && count <= A.cache_cap && !dense);
+    if (slots) return;                      // cache-sized lists are never this long
+    const int32_t* in = c.implicit ? nullptr : (c.cur ? A.list1 : A.list0) + (size_t)q * A.N;
+    const int out_sel = c.implicit ? 0 : (c.cur ^ 1);
+    int32_t* out = (out_sel ? A.list1 : A.list0) + (size_t)q * A.N;
+    const float2* stat = A.stat + (size_t)q * A.N;
+    const float2* bat = A.stat2 + (size_t)q * A.N;
+    const bool fold = dense && in != nullptr;
+    const int n = A.n, T = A.T;
+    const float kappa = A.kappa, a = A.a, b = A.b;
+
+    auto stat_of = [&](int e) -> float2 {
+        float2 st = stat[e];
+        if (fold) {
+            const float2 bb = bat[e];
+            merge_stats(st.x, st.y, A.n_prev, bb.x, bb.y, A.nb);
+        }
+        return st;
+    };
+    auto key_s = [&](int j) -> uint32_t {
+        const int pos = sample_pos(j, count);
+        const float2 st = stat_of(in ? in[pos] : pos);
+        float lcb, ucb;
+        interval(st.x, st.y, n, T, kappa, a, b, lcb, ucb);
+        return float_key(lcb);
+    };
+    const float tau_lo = key_float(block_kth_largest_sample(A.K, key_s, hist, pick));
+    const FastUcb fk = fast_ucb_consts(n, T, kappa, b);
+    const float tau_fast = tau_lo - (1e-3f + 1e-5f * fabsf(tau_lo));
+
+    const int len = seg_len(count, A.n_seg);
+    const int lo = sg * len;
+    const int hi = lo + len < count ? lo + len : count;
+    const size_t tro = ((size_t)(A.r - 1) * A.nq + q) * A.N;
+    constexpr int ITEMS = SEL_ITEMS_WIDE;
+    constexpr int CHUNK = SEL_THREADS * ITEMS;
+    const int t0 = threadIdx.x * ITEMS;
+    auto load_e = [&](int start, int (&e)[ITEMS]) {
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u) {
+            const int idx = start + t0 + u;
+            e[u] = idx < hi ? (in ? in[idx] : idx) : 0;
+        }
+    };
+    auto load_s = [&](int start, const int (&e)[ITEMS], float2 (&st)[ITEMS], float2 (&bb)[ITEMS]) {
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u) {
+            const bool ok = start + t0 + u < hi;
+            st[u] = ok ? stat[e[u]] : make_float2(0.f, 0.f);
+            bb[u] = (ok && fold) ? bat[e[u]] : make_float2(0.f, 0.f);
+        }
+    };
+    int base = 0;
+    int e[ITEMS], e_next[ITEMS];
+    float2 st[ITEMS], bb[ITEMS];
+    load_e(lo, e);
+    load_s(lo, e, st, bb);
+    load_e(lo + CHUNK, e_next);
+    for (int start = lo; start < hi; start += CHUNK) {
+        const int i0 = start + t0;
+        int e_next2[ITEMS];
+        float2 st_next[ITEMS], bb_next[ITEMS];
+        load_s(start + CHUNK, e_next, st_next, bb_next);
+        load_e(start + 2 * CHUNK, e_next2);
+        unsigned keep = 0;
+        if (A.tr_lcb || fold) {
+            // exact intervals: the trace records every dropped entry's interval
+#pragma unroll
+            for (int u = 0; u < ITEMS; ++u) {
+                if (i0 + u < hi) {
+                    if (fold) merge_stats(st[u].x, st[u].y, A.n_prev, bb[u].x, bb[u].y, A.nb);
+                    float lcb, ucb;
+                    interval(st[u].x, st[u].y, n, T, kappa, a, b, lcb, ucb);
+                    const bool kp = ucb >= tau_lo;
+                    keep |= (kp ? 1u : 0u) << u;
+                    if (A.tr_lcb && !kp) {
+                        A.tr_lcb[tro + e[u]] = lcb;
+                        A.tr_ucb[tro + e[u]] = ucb;
+                        A.tr_alive[tro + e[u]] = 0;
+                    }
+                }
+            }
+        } else {
+            // A pre-filter may keep too much but never too little: the UCB is evaluated with
+            // reciprocal multiplications and the hardware square root, and compared with the
+            // threshold lowered by far more than the error of that shortcut (values are of
+            // size <= T; the shortcut is good to a few ulps).
+#pragma unroll
+            for (int u = 0; u < ITEMS; ++u) {
+                if (i0 + u < hi) {
+                    const float ucb = fast_ucb(st[u].x, st[u].y, n, T, fk);
+                    keep |= (ucb >= tau_fast ? 1u : 0u) << u;
+                }
+            }
+        }
+        if (__syncthreads_or(keep != 0)) {
+            int total;
+            int pos = lo + base + block_excl_scan(__popc(keep), wtot, total);
+#pragma unroll
+            for (int u = 0; u < ITEMS; ++u)
+                if (keep & (1u << u)) out[pos++] = e[u];
+            base += total;
+        }
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u) {
+            e[u] = e_next[u];
+            st[u] = st_next[u];
+            bb[u] = bb_next[u];
+            e_next[u] = e_next2[u];
+        }
+    }
+    if (threadIdx.x == 0) A.seg_cnt[(size_t)q * SEG_MAX + sg] = base;
 }
 
 hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
@@ -814,6 +1095,15 @@ hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
     A.tr_lcb = tr.lcb;
     A.tr_ucb = tr.ucb;
     A.tr_alive = tr.alive;
+    // lists longer than the pre-filter limit are first cut down by several workgroups per query
+    A.n_seg = 0;
+    A.seg_cnt = W.seg_cnt;
+    if (P.N > SEL_PREFILTER_MIN) {
+        int n_seg = 512 / P.nq;      // about two workgroups per CU in total
+        n_seg = n_seg < 2 ? 2 : (n_seg > SEG_MAX ? SEG_MAX : n_seg);
+        A.n_seg = n_seg;
+        k_select_segments<<<dim3(n_seg, P.nq), SEL_THREADS, 0, st>>>(A);
+    }
     k_select_prune<<<P.nq, SEL_THREADS, 0, st>>>(A);
     return hipGetLastError();
 }
@@ -834,7 +1124,57 @@ struct TopkArgs {
     int K;
     int64_t* out_ids;
     float* out_scores;
+    int n_seg;             // > 0: k_topk_segments has pre-filtered the positions (ctl == nullptr)
+    int32_t* seg_cnt;      // [nq][SEG_MAX]
 };
+
+// The pre-filter of k_topk for all-documents inputs, spread over n_seg workgroups per query:
+// same sample threshold in every workgroup, one streaming pass over the workgroup's segment,
+// candidate positions in order at the segment's start of the scratch list.
+__global__ __launch_bounds__(SEL_THREADS) void k_topk_segments(TopkArgs A) {
+    __shared__ uint32_t hist[2048];
+    __shared__ int pick[2];
+    __shared__ int wtot[SEL_WAVES];
+    const int q = blockIdx.y, sg = blockIdx.x;
+    const int count = (int)A.N;
+    if (count <= SEL_PREFILTER_MIN) return;
+    const float* vals = A.vals + (size_t)q * A.N;
+    int32_t* tmp = A.list0 + (size_t)q * A.N;
+    const int Kq = A.K < count ? A.K : count;
+    auto key_s = [&](int j) -> uint32_t { return float_key(vals[sample_pos(j, count)]); };
+    const uint32_t lo_key = block_kth_largest_sample(Kq, key_s, hist, pick);
+    const int len = seg_len(count, A.n_seg);
+    const int lo = sg * len;
+    const int hi = lo + len < count ? lo + len : count;
+    constexpr int ITEMS = SEL_ITEMS_WIDE;
+    constexpr int CHUNK = SEL_THREADS * ITEMS;
+    const int t0 = threadIdx.x * ITEMS;
+    int base = 0;
+    float v[ITEMS];
+#pragma unroll
+    for (int u = 0; u < ITEMS; ++u) v[u] = lo + t0 + u < hi ? vals[lo + t0 + u] : 0.f;
+    for (int start = lo; start < hi; start += CHUNK) {
+        const int i0 = start + t0;
+        float v_next[ITEMS];
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u) v_next[u] = i0 + CHUNK + u < hi ? vals[i0 + CHUNK + u] : 0.f;
+        unsigned keep = 0;
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u)
+            if (i0 + u < hi && float_key(v[u]) >= lo_key) keep |= 1u << u;
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u) v[u] = v_next[u];
+        if (__syncthreads_or(keep != 0)) {
+            int total;
+            int pos = lo + base + block_excl_scan(__popc(keep), wtot, total);
+#pragma unroll
+            for (int u = 0; u < ITEMS; ++u)
+                if (keep & (1u << u)) tmp[pos++] = i0 + u;
+            base += total;
+        }
+    }
+    if (threadIdx.x == 0) A.seg_cnt[(size_t)q * SEG_MAX + sg] = base;
+}
 
 __global__ __launch_bounds__(SEL_THREADS) void k_topk(TopkArgs A) {
     __shared__ uint32_t hist[2048];
@@ -863,10 +1203,13 @@ __global__ __launch_bounds__(SEL_THREADS) void k_topk(TopkArgs A) {
         // the K-th largest value of a strided sample, which cannot exceed the true K-th
         const int32_t* cand = nullptr;
         int ncand = count;
-        if (count > SEL_PREFILTER_MIN) {
+        if (A.n_seg > 0 && !A.ctl && count > SEL_PREFILTER_MIN) {
+            ncand = merge_segments(scratch, A.seg_cnt + (size_t)q * SEG_MAX, count, A.n_seg);
+            cand = scratch;
+        } else if (count > SEL_PREFILTER_MIN) {
             int32_t* tmp = scratch;
             auto key_s = [&](int j) -> uint32_t { return float_key(vals[sample_pos(j, count)]); };
-            const uint32_t lo = block_kth_largest(SEL_SAMPLE, Kq, key_s, hist, pick);
+            const uint32_t lo = block_kth_largest_sample(Kq, key_s, hist, pick);
             int base = 0;
             const int t0 = threadIdx.x * SEL_ITEMS_WIDE;
             float v[SEL_ITEMS_WIDE];                       // the next chunk's values are fetched
@@ -978,6 +1321,14 @@ hipError_t launch_topk(const Problem& P, const Work& W, bool use_ctl, const floa
     A.K = K;
     A.out_ids = out_ids;
     A.out_scores = out_scores;
+    A.n_seg = 0;
+    A.seg_cnt = W.seg_cnt;
+    if (!use_ctl && P.N > SEL_PREFILTER_MIN) {
+        int n_seg = 512 / P.nq;
+        n_seg = n_seg < 2 ? 2 : (n_seg > SEG_MAX ? SEG_MAX : n_seg);
+        A.n_seg = n_seg;
+        k_topk_segments<<<dim3(n_seg, P.nq), SEL_THREADS, 0, st>>>(A);
+    }
     k_topk<<<P.nq, SEL_THREADS, 0, st>>>(A);
     return hipGetLastError();
 }

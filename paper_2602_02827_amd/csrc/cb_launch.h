@@ -24,6 +24,7 @@ struct Work {
     float2* stat;         // [nq][N] per (query, doc): revealed sum, centred sum of squares
     float2* stat2;        // [nq][N] batch (sum, centred squares) of a later round's dense pass
     unsigned long long* pairs;   // [R+2] pairs[r]: (query, doc) pairs round r would have to gather
+    int32_t* seg_cnt;     // [nq][64] candidates per segment of a segmented pre-filter
     float* rescored;      // [nq][N] exact score of the k-th survivor
     float* scores;        // [nq][N] Full-MaxSim scores when the caller keeps none
     int32_t* cnt_hist;    // [(R+1)][nq]

@@ -351,6 +351,22 @@ def test_long_lists_take_the_sampled_prefilter(B, S, oracle_mod, K):
     _run_colbandit_case(B, oracle_mod, w, K, 5, 4, 0.2, seed=2)
 
 
+@pytest.mark.parametrize("nq", [1, 3])
+def test_long_lists_stay_long_under_a_conservative_radius(B, S, oracle_mod, nq):
+    """alpha_ef = 1 keeps most of 150,000 documents alive for several rounds: explicit lists
+    longer than the pre-filter limit, cut down by several workgroups per query, revealed by the
+    corpus pass (statistics merged for the candidates only) or by gathers - same decisions."""
+    rng = np.random.default_rng(78)
+    w = _custom(S, rng.integers(1, 4, 150000).tolist(), nq, 32, 128, "bf16", 37)
+    runs = [B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 1.0, 0.01, 5, 6, trace=True, later_rounds=m)
+            for m in (1, 2)]
+    torch.cuda.synchronize()
+    surv = runs[0]["stats"][0]["survivors"]
+    assert len(surv) > 3 and surv[2] > 131072, surv          # long lists beyond round 1
+    _same_run(runs[0], runs[1])
+    _run_colbandit_case(B, oracle_mod, w, 5, 5, 4, 1.0, seed=6, later_rounds=1)
+
+
 def test_long_lists_with_massive_ties(B, S):
     """150,000 documents that are copies of 40 distinct ones: the K-th score is shared by
     thousands; ties resolve to the lowest indices."""
