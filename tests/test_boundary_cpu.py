@@ -108,6 +108,46 @@ def test_topk_argument_errors(B):
     assert _call_topk(B, opts=o) == -5
 
 
+def test_coarse_pass_argument_errors(B):
+    # opts of colbandit_topk
+    assert _call_topk(B, opts=B.ColbanditOpts(later_rounds=3)) == -3
+    assert _call_topk(B, opts=B.ColbanditOpts(later_rounds=-1)) == -3
+    assert _call_topk(B, opts=B.ColbanditOpts(docs_i8=0x7000)) == -1            # codes without their scale
+    assert _call_topk(B, opts=B.ColbanditOpts(docs_i8=0x7004, docs_scale=0x8000)) == -6
+    assert _call_topk(B, opts=B.ColbanditOpts(docs_i8=0x7000, docs_scale=0x8002)) == -6
+    assert _call_topk(B, opts=B.ColbanditOpts(docs_i8=0x7000, docs_scale=0x8000, coarse_permille=1001)) == -3
+    assert _call_topk(B, opts=B.ColbanditOpts(docs_i8=0x7000, docs_scale=0x8000, coarse_permille=-1)) == -3
+
+    # colbandit_quantize_i8
+    L = B.lib()
+    def quant(x=0x1000, dt=1, nseg=1, rows=10, d=128, pm=999, codes=0x2000, scales=0x3000,
+              ws=0x10000, wsb=1 << 30):
+        return L.colbandit_quantize_i8(x, dt, nseg, rows, d, pm, codes, scales, ws, wsb, None)
+    assert quant(x=None) == -1 and quant(codes=None) == -1 and quant(scales=None) == -1
+    assert quant(nseg=0) == -2 and quant(rows=0) == -2 and quant(d=0) == -2 and quant(dt=5) == -2
+    assert quant(nseg=70000) == -2
+    assert quant(pm=0) == -3 and quant(pm=1001) == -3
+    assert quant(x=0x1008) == -6 and quant(scales=0x3001) == -6
+    assert quant(ws=None) == -1 and quant(ws=0x10001) == -6 and quant(wsb=16) == -5
+    assert L.colbandit_quantize_workspace_bytes(0) == 0
+    w1, w4 = L.colbandit_quantize_workspace_bytes(1), L.colbandit_quantize_workspace_bytes(4)
+    assert 0 < w1 < w4 and w1 % 256 == 0
+
+    # colbandit_coarse_maxsim
+    def coarse(**kw):
+        a = dict(Q=0x1000, nq=1, T=32, d=128, dt=1, d8=0x2000, ds=0x2100, off=0x3000, N=10, total=400,
+                 pm=999, scores=0x4000, cells=None, qc=None, qs=None, ws=0x10000, wsb=1 << 40)
+        a.update(kw)
+        return L.colbandit_coarse_maxsim(a["Q"], a["nq"], a["T"], a["d"], a["dt"], a["d8"], a["ds"],
+                                         a["off"], a["N"], a["total"], a["pm"], a["scores"], a["cells"],
+                                         a["qc"], a["qs"], a["ws"], a["wsb"], None)
+    assert coarse(Q=None) == -1 and coarse(d8=None) == -1 and coarse(ds=None) == -1
+    assert coarse(scores=None) == -1
+    assert coarse(pm=0) == -3
+    assert coarse(N=0) == -2 and coarse(d=96) == -4
+    assert coarse(wsb=1024) == -5
+
+
 def test_workspace_and_trace_sizes(B):
     assert B.colbandit_workspace_bytes(0, 32, 128, 10, 100) == 0
     assert B.colbandit_workspace_bytes(1, 32, 128, 10, 5) == 0
