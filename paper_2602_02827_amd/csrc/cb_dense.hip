@@ -15,9 +15,10 @@
 //     a token is read from memory once per workgroup and from LDS once per wavefront.
 //     Rows are stored with their 16-byte pieces XOR-swizzled by the row index, which
 //     spreads the 16 rows of an operand block over all banks.
-//   * Blocks of 16 tokens are aligned to the start of each document; a short last block
-//     re-reads the document's last token (duplicates do not change a max), so the
-//     epilogue needs no masking and documents of any length >= 1 are handled.
+//   * The chunk's tokens form one stream of aligned 16-token blocks, whatever the document
+//     boundaries, so no token is multiplied twice.  A block inside one document folds into
+//     the running maxima directly; where a document ends inside a block the fold is split
+//     by accumulator row (block_mma_split).  Documents of any length >= 1 are handled.
 //   * Workgroup ids are laid out so that the column groups of one token chunk run on the
 //     same XCD and share its L2.
 #include "cb_launch.h"
@@ -240,7 +241,6 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
     };
 
     // one block of 16 tokens against all NT column tiles
-    auto compute = [&](const F& a) { block_mma<NT>(a, bq, h); };
     // ---- stage bookkeeping.  `published` stages are visible to every wavefront, stage
     // `published` (if any) is in flight.  All four wavefronts walk the same documents and
     // blocks, so they call stage_advance at the same points and its barrier matches up.
@@ -262,30 +262,18 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
         avail = published * STAGE_ROWS < ntok ? published * STAGE_ROWS : ntok;
     };
 
-    // ---- block stream: the load cursor walks documents and their 16-token blocks and
-    // issues each block's A-operand reads one block ahead of the MFMAs that use them.
-    int ldoc = i0 - 1, lend = 0, lcur = 0;      // load cursor: document, its end, next row
-    struct BlockInfo {
-        int doc;       // document the block belongs to (-1: no block, stream exhausted)
-        bool last;     // last block of its document
-    };
-    auto next_block = [&](F& a) -> BlockInfo {
-        while (lcur >= lend) {                  // next document (empty ones yield no block)
-            ++ldoc;
-            if (ldoc >= i1) return BlockInfo{-1, false};
-            lcur = lend;
-            lend = rel_off(ldoc + 1);
-        }
-        const int start = lcur;
-        const int end = start + 16 < lend ? start + 16 : lend;
+    // ---- block stream.  The chunk's tokens are one stream cut into aligned blocks of 16 rows,
+    // whatever the document boundaries: no row is multiplied twice.  A block that lies inside
+    // one document (most do) folds into the running maxima as it is; a block in which a
+    // document ends is folded in two parts, rows before the boundary into the ending document
+    // and the rows after it into fresh maxima for the next one (block_mma_split); further
+    // boundaries in the same block repeat the block's MFMAs for the next part.  The rows past
+    // the chunk's end in its last block repeat the last token.
+    auto load_block = [&](F& a, int bs) {
+        const int end = bs + 16 < ntok ? bs + 16 : ntok;
         while (end > avail) stage_advance();    // end <= ntok, so this stops at the last stage
-        // Lane -> row: any one-to-one assignment works (the max runs over all 16 rows).  LDS
-        // serves a 16-byte read per lane fastest when lanes 2j and 2j+1 hit an aligned pair of
-        // pieces; with the row-keyed swizzle that means an aligned row pair, so on an odd block
-        // start lane 0 takes the block's last row.  A short last block repeats the document's
-        // last token in the lanes past its end (a duplicate cannot change a max).
-        int row = (start & 1) ? ((col == 0) ? start + 15 : start - 1 + col) : start + col;
-        row = row < end ? row : end - 1;
+        int row = bs + col;
+        row = row < ntok ? row : ntok - 1;
         const char* rp = ring + (row & (RING_ROWS - 1)) * ROWB;
         const int sw = (row >> KEY_SHIFT) & (NCH - 1);
 #pragma unroll
@@ -293,35 +281,53 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
             using piece_t = __remove_reference_t(decltype(a.v[0]));
             a.v[ks] = *(const piece_t*)(rp + (((ks * 4 + kg) ^ sw) * 16));
         }
-        lcur = end;
-        return BlockInfo{ldoc, end == lend};
     };
-
-    // ---- consumer: MFMAs of block k overlap the operand reads of block k+1; a document's
-    // epilogue runs after its last block.  Documents without tokens (a precondition
-    // violation) still get their -inf result.
-    int done_doc = i0 - 1;                      // documents < = done_doc have been finalized
-    auto retire = [&](const BlockInfo& b) {
-        if (b.last) {
-            while (done_doc + 1 < b.doc) finalize(++done_doc);   // empty documents in between
-            finalize(b.doc);
-            done_doc = b.doc;
+    int doc = i0;                   // document whose maxima are being accumulated
+    int dend = rel_off(i0 + 1);     // its end, relative to the chunk
+    const int rowbase = 4 * kg;
+    auto process = [&](const F& a, int bs) {
+        int b = dend - bs;
+        if (b > 16 || doc >= i1) {              // the block lies inside the current document
+            block_mma<NT>(a, bq, h);
+            return;
+        }
+        int lo = 0;
+        for (;;) {
+            V hB[NT];
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt) hB[tt] = lowest_val<V>();
+            const int bb = b < lo ? lo : b;     // offsets that run backwards: an empty part
+            block_mma_split<NT>(a, bq, h, hB, lo, bb, rowbase);
+            finalize(doc);
+            ++doc;
+            if (doc >= i1) return;
+            lo = bb;
+            dend = rel_off(doc + 1);
+            b = dend - bs;
+            if (b > 16) {                       // the rest of the block starts the next document
+#pragma unroll
+                for (int tt = 0; tt < NT; ++tt) h[tt] = hB[tt];
+                return;
+            }
         }
     };
+
+    // ---- consumer: the MFMAs of block k overlap the operand reads of block k+1
     F a0, a1;
-    BlockInfo b0 = next_block(a0), b1;
-    while (b0.doc >= 0) {
-        b1 = next_block(a1);
+    int bs = 0;
+    load_block(a0, 0);
+    while (bs < ntok) {
+        if (bs + 16 < ntok) load_block(a1, bs + 16);
         __builtin_amdgcn_sched_barrier(0);      // keep the reads of the next block up here
-        compute(a0);
-        retire(b0);
-        if (b1.doc < 0) break;
-        b0 = next_block(a0);
+        process(a0, bs);
+        bs += 16;
+        if (bs >= ntok) break;
+        if (bs + 16 < ntok) load_block(a0, bs + 16);
         __builtin_amdgcn_sched_barrier(0);
-        compute(a1);
-        retire(b1);
+        process(a1, bs);
+        bs += 16;
     }
-    while (done_doc + 1 < i1) finalize(++done_doc);             // trailing empty documents
+    while (doc < i1) finalize(doc++);           // documents without tokens at the chunk's end
 }
 
 // ---- first document of every token chunk: chunk_doc[c] = min{ i : off[i] >= c*C }

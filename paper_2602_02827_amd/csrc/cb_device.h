@@ -195,6 +195,50 @@ __device__ __forceinline__ void block_mma(const F& a, const F (&bq)[NT],
     }
 }
 
+// The same block when a document ends inside it: rows [lo, b) of the block still belong to the
+// current document and go into hA, rows [b, 16) into hB (the start of the next document); rows
+// below lo were consumed by earlier documents.  inA[i] / inB[i]: membership of this lane's
+// accumulator row 4*(lane>>4)+i.
+template <class V, class ACC>
+__device__ __forceinline__ void fold_split(V& hA, V& hB, const ACC& c, const bool (&inA)[4],
+                                           const bool (&inB)[4]) {
+    const V low = lowest_val<V>();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const V va = inA[i] ? c[i] : low;
+        const V vb = inB[i] ? c[i] : low;
+        hA = hA > va ? hA : va;
+        hB = hB > vb ? hB : vb;
+    }
+}
+template <int NT, class F>
+__device__ __forceinline__ void block_mma_split(const F& a, const F (&bq)[NT],
+                                                typename F::val_t (&hA)[NT],
+                                                typename F::val_t (&hB)[NT], int lo, int b,
+                                                int rowbase) {
+    using acc_t = typename F::acc_t;
+    bool inA[4], inB[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = rowbase + i;
+        inA[i] = r >= lo && r < b;
+        inB[i] = r >= b;
+    }
+    if constexpr (NT == 1) {
+        acc_t acc = {0, 0, 0, 0};
+        F::mma(acc, a, bq[0]);
+        fold_split(hA[0], hB[0], acc, inA, inB);
+    } else {
+#pragma unroll
+        for (int p = 0; p < NT / 2; ++p) {
+            acc_t c0 = {0, 0, 0, 0}, c1 = c0;
+            F::mma2(c0, c1, a, bq[2 * p], bq[2 * p + 1]);
+            fold_split(hA[2 * p], hB[2 * p], c0, inA, inB);
+            fold_split(hA[2 * p + 1], hB[2 * p + 1], c1, inA, inB);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------
 // Cross-lane helpers.  A wavefront is four rows of 16 lanes; row = lane >> 4 is the
 // accumulator's row group, col = lane & 15 its column.  DPP moves data inside a row,
