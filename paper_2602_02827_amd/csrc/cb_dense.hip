@@ -67,7 +67,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
     __shared__ __attribute__((aligned(16))) char ring[RING_ROWS * ROWB];
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, in an SGPR
     const int col = lane & 15;
     const int kg = lane >> 4;
 
@@ -119,13 +119,32 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
     const char* src = (const char*)A.docs + (size_t)tok_begin * ROWB;
     constexpr int ROWS_PER_LOAD = 64 / NCH;
     constexpr int LOADS_PER_WAVE = STAGE_ROWS / ROWS_PER_LOAD / 4;
+    // A lane's place inside a load does not depend on the stage or on the load's number (both
+    // move the row by multiples of the swizzle period): row wave*ROWS_PER_LOAD + lane/NCH of the
+    // load group, piece (lane % NCH) ^ key(row).  A complete stage therefore needs no per-lane
+    // address arithmetic at all: uniform base + this constant offset.
+    const int lrow0 = wave * ROWS_PER_LOAD + lane / NCH;
+    const unsigned fetch_off =
+        (unsigned)(lrow0 * ROWB + (((lane & (NCH - 1)) ^ ((lrow0 >> KEY_SHIFT) & (NCH - 1))) * 16));
     auto stage_fetch = [&](int s) {
+        if ((s + 1) * STAGE_ROWS <= ntok) {
+#pragma unroll
+            for (int i = 0; i < LOADS_PER_WAVE; ++i) {
+                const int r0 = s * STAGE_ROWS + i * 4 * ROWS_PER_LOAD;               // uniform
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(src + (size_t)r0 * ROWB + fetch_off),
+                    (__attribute__((address_space(3))) void*)(ring + ((r0 + wave * ROWS_PER_LOAD) & (RING_ROWS - 1)) * ROWB),
+                    16, 0, 0);
+            }
+            return;
+        }
+        // the chunk's last, incomplete stage: rows past the end are clamped (they are never read)
 #pragma unroll
         for (int i = 0; i < LOADS_PER_WAVE; ++i) {
             const int rbase = s * STAGE_ROWS + (i * 4 + wave) * ROWS_PER_LOAD;   // wave-uniform
             if (rbase < ntok) {
                 const int lrow = rbase + lane / NCH;                  // the LDS row this lane fills
-                const int grow = lrow < ntok ? lrow : ntok - 1;       // rows past the end are never read
+                const int grow = lrow < ntok ? lrow : ntok - 1;
                 const int c = (lane & (NCH - 1)) ^ ((lrow >> KEY_SHIFT) & (NCH - 1));
                 __builtin_amdgcn_global_load_lds(
                     (const __attribute__((address_space(1))) void*)(src + (size_t)grow * ROWB + c * 16),
@@ -269,18 +288,29 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
     // and the rows after it into fresh maxima for the next one (block_mma_split); further
     // boundaries in the same block repeat the block's MFMAs for the next part.  The rows past
     // the chunk's end in its last block repeat the last token.
+    // a lane's operand pieces inside an aligned block: row `col` of the block, piece
+    // (ks*4 + kg) ^ key(row); the key does not depend on the block (blocks start at multiples
+    // of 16 rows)
+    unsigned blk_off[F::KS];
+#pragma unroll
+    for (int ks = 0; ks < F::KS; ++ks)
+        blk_off[ks] = (unsigned)(col * ROWB + (((ks * 4 + kg) ^ ((col >> KEY_SHIFT) & (NCH - 1))) * 16));
     auto load_block = [&](F& a, int bs) {
+        using piece_t = __remove_reference_t(decltype(a.v[0]));
         const int end = bs + 16 < ntok ? bs + 16 : ntok;
         while (end > avail) stage_advance();    // end <= ntok, so this stops at the last stage
-        int row = bs + col;
+        if (bs + 16 <= ntok) {
+            const char* rp = ring + (bs & (RING_ROWS - 1)) * ROWB;       // uniform
+#pragma unroll
+            for (int ks = 0; ks < F::KS; ++ks) a.v[ks] = *(const piece_t*)(rp + blk_off[ks]);
+            return;
+        }
+        int row = bs + col;                      // the chunk's last block: repeat the last token
         row = row < ntok ? row : ntok - 1;
         const char* rp = ring + (row & (RING_ROWS - 1)) * ROWB;
         const int sw = (row >> KEY_SHIFT) & (NCH - 1);
 #pragma unroll
-        for (int ks = 0; ks < F::KS; ++ks) {
-            using piece_t = __remove_reference_t(decltype(a.v[0]));
-            a.v[ks] = *(const piece_t*)(rp + (((ks * 4 + kg) ^ sw) * 16));
-        }
+        for (int ks = 0; ks < F::KS; ++ks) a.v[ks] = *(const piece_t*)(rp + (((ks * 4 + kg) ^ sw) * 16));
     };
     int doc = i0;                   // document whose maxima are being accumulated
     int dend = rel_off(i0 + 1);     // its end, relative to the chunk
@@ -292,6 +322,16 @@ __global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
             return;
         }
         int lo = 0;
+        if (b == 16) {                          // it ends exactly with the block: no split needed
+            block_mma<NT>(a, bq, h);
+            finalize(doc);
+            ++doc;
+            if (doc >= i1) return;
+            dend = rel_off(doc + 1);
+            b = dend - bs;
+            if (b > 16) return;                 // the usual case: the next document has tokens
+            lo = 16;
+        }
         for (;;) {
             V hB[NT];
 #pragma unroll

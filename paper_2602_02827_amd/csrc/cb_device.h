@@ -148,6 +148,8 @@ template <class V> __device__ __forceinline__ V lowest_val();
 template <> __device__ __forceinline__ float lowest_val<float>() { return -__builtin_inff(); }
 template <> __device__ __forceinline__ int lowest_val<int>() { return (int)0x80000000; }
 __device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
+__device__ __forceinline__ float vmax(float a, float b) { return fmaxf(a, b); }
+__device__ __forceinline__ int vmax(int a, int b) { return a > b ? a : b; }
 
 // Accumulator layout of the 16x16 MFMAs: lane holds column (lane & 15) and rows
 // 4*(lane >> 4) + {0,1,2,3}.  Rows are document tokens, columns are query rows.
@@ -203,13 +205,15 @@ template <class V, class ACC>
 __device__ __forceinline__ void fold_split(V& hA, V& hB, const ACC& c, const bool (&inA)[4],
                                            const bool (&inB)[4]) {
     const V low = lowest_val<V>();
+    V va[4], vb[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const V va = inA[i] ? c[i] : low;
-        const V vb = inB[i] ? c[i] : low;
-        hA = hA > va ? hA : va;
-        hB = hB > vb ? hB : vb;
+        va[i] = inA[i] ? c[i] : low;
+        vb[i] = inB[i] ? c[i] : low;
     }
+    // three-input maxima, as in fold_max
+    hA = vmax(vmax(hA, vmax(vmax(va[0], va[1]), va[2])), va[3]);
+    hB = vmax(vmax(hB, vmax(vmax(vb[0], vb[1]), vb[2])), vb[3]);
 }
 template <int NT, class F>
 __device__ __forceinline__ void block_mma_split(const F& a, const F (&bq)[NT],
