@@ -113,6 +113,27 @@ def test_full_maxsim_fp32_ragged_and_d64(B, S, oracle_mod):
         np.testing.assert_allclose(r["scores"].cpu().numpy(), Sor, rtol=1e-5, atol=1e-6)
 
 
+def test_documents_without_tokens_get_minus_infinity_and_disturb_nothing(B, S, oracle_mod):
+    """Empty documents violate the input contract (colbandit_validate_offsets reports them), but
+    the scoring kernels must stay in bounds: such a document scores -inf and its neighbours,
+    which share 16-token blocks with it, keep their exact scores."""
+    rng = np.random.default_rng(41)
+    lengths = rng.integers(1, 40, 400).tolist()
+    for i in (0, 1, 7, 8, 9, 100, 250, 251, 252, 399):
+        lengths[i] = 0
+    w = _custom(S, lengths, 3, 32, 128, "bf16", 43)
+    full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=0)
+    torch.cuda.synchronize()
+    got = full["scores"].cpu().numpy()
+    keep = [i for i, n in enumerate(lengths) if n > 0]
+    E, off = w.host_docs(keep)
+    Qh = w.host_queries()
+    for q in range(w.nq):
+        want = oracle_mod.row_sums(oracle_mod.maxsim_cells(Qh[q], E, off))
+        np.testing.assert_allclose(got[q][keep], want, rtol=TOL["bf16"], atol=1e-4)
+        assert np.all(np.isneginf(got[q][[i for i, n in enumerate(lengths) if n == 0]]))
+
+
 def test_topk_ties_resolve_to_lower_index(B, S):
     # documents 10.. are exact copies of documents 0..9 -> exact score ties
     base = _custom(S, [20] * 10, 2, 32, 128, "bf16", 3)
