@@ -26,8 +26,16 @@
 namespace cb {
 
 constexpr int DENSE_THREADS = 256;
-constexpr int STAGE_ROWS = 64;
-constexpr int RING_ROWS = 256;   // 4 stages
+// Ring geometry: four stages.  Kernels with few column tiles per wavefront (small query
+// batches: bound by memory, little register use) take 32-row stages, so that four workgroups fit
+// a CU instead of two and more wavefronts hide the latencies; the others take 64-row stages.
+template <int NT, int ROWB> struct RingShape {
+    static constexpr int ROWS_PER_LOAD = 64 / (ROWB / 16);
+    static constexpr bool SMALL = NT <= 4 && 32 / ROWS_PER_LOAD / 4 >= 1;
+    static constexpr int STAGE_ROWS = SMALL ? 32 : 64;
+    static constexpr int RING_ROWS = 4 * STAGE_ROWS;
+    static constexpr int MIN_BLOCKS = SMALL ? (NT <= 2 ? 4 : 3) : 2;
+};
 
 struct DenseArgs {
     const void* Q;
@@ -55,8 +63,12 @@ struct DenseArgs {
 };
 
 template <typename Tag, int D, int NT, int TQ, bool REVEAL>
-__global__ __launch_bounds__(DENSE_THREADS, 2) void k_dense(DenseArgs A) {
+__global__ __launch_bounds__(DENSE_THREADS, (RingShape<NT, D * Frag<Tag, D>::ELEM_BYTES>::MIN_BLOCKS))
+void k_dense(DenseArgs A) {
     using F = Frag<Tag, D>;
+    using RS = RingShape<NT, D * F::ELEM_BYTES>;
+    constexpr int STAGE_ROWS = RS::STAGE_ROWS;
+    constexpr int RING_ROWS = RS::RING_ROWS;
     using V = typename F::val_t;           // float, or int for int8 codes
     constexpr bool CODES = !__is_same(V, float);
     constexpr int ROWB = D * F::ELEM_BYTES;   // bytes per token row

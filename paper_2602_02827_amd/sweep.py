@@ -3,6 +3,7 @@
     python -m paper_2602_02827_amd.sweep --config 4 --alpha 0.05 0.1 0.2 0.5 1.0 --K 1 5 10 50
     python -m paper_2602_02827_amd.sweep --config 2 --K 100 500 1000 --M 0 5 10
     python -m paper_2602_02827_amd.sweep --config 2 --nq 1            # single-query latency
+    python -m paper_2602_02827_amd.sweep --config 2 --nq 1 --int8     # ... with int8 elimination rounds
 
 Prints one JSON line per (K, alpha_ef, M): batch latency of colbandit_full_maxsim and of
 colbandit_topk (events around `--reps` back-to-back asynchronous calls), coverage
@@ -27,6 +28,8 @@ def main(argv=None):
     ap.add_argument("--M", type=int, nargs="+", default=[5])
     ap.add_argument("--B", type=int, default=4)
     ap.add_argument("--reps", type=int, default=3)
+    ap.add_argument("--int8", action="store_true",
+                    help="run the elimination rounds on int8 codes of the corpus (coded once, untimed)")
     args = ap.parse_args(argv)
 
     import numpy as np
@@ -38,6 +41,11 @@ def main(argv=None):
     w = synth.config(args.config, device="cuda", scale=args.scale, nq=args.nq)
     nq, T, d, N, total = w.nq, w.T, w.d, w.N, w.total_tokens
     ws = B.new_workspace(nq, T, d, N, total, "cuda")
+
+    ckw = {}
+    if args.int8:
+        d8, ds = B.colbandit_quantize_i8(w.docs)
+        ckw = {"docs_i8": d8, "docs_scale": ds}
 
     def timed(fn):
         fn()
@@ -58,7 +66,7 @@ def main(argv=None):
         for alpha in args.alpha:
             for M in args.M:
                 run = lambda stats=False: B.colbandit_topk(w.Q, w.docs, w.offsets, K, alpha, w.delta, M,
-                                                           w.seed, B=args.B, workspace=ws, want_stats=stats)
+                                                           w.seed, B=args.B, workspace=ws, want_stats=stats, **ckw)
                 ms_cb = timed(run)
                 res = run(True)
                 torch.cuda.synchronize()
@@ -68,7 +76,7 @@ def main(argv=None):
                 cov = sum(s["cells_unique"] for s in st) / (float(nq) * N * T)
                 print(json.dumps({
                     "workload": w.name, "n_queries": nq, "N": N, "T": T, "d": d, "K": K, "alpha_ef": alpha,
-                    "M": M, "B": args.B, "full_ms": round(ms_full, 3), "colbandit_ms": round(ms_cb, 3),
+                    "M": M, "B": args.B, "reveals": "int8" if args.int8 else w.dtype, "full_ms": round(ms_full, 3), "colbandit_ms": round(ms_cb, 3),
                     "speedup": round(ms_full / ms_cb, 2), "coverage": round(cov, 4),
                     "overlap_at_k": round(overlap, 4),
                     "mean_rounds": round(float(np.mean([s["rounds"] for s in st])), 2),
