@@ -102,6 +102,7 @@ void k_dense(DenseArgs A) {
     const int ntok = (int)(tok_end - tok_begin);
     if (ntok <= 0) return;
 
+    const int lgG = REVEAL ? 31 - __builtin_clz(A.G > 0 ? A.G : 1) : 0;   // G is a power of two
     // ---- query rows of this wavefront's column tiles -> B fragments (registers)
     const int tile0 = (group * 4 + wave) * NT;
     F bq[NT];
@@ -111,8 +112,8 @@ void k_dense(DenseArgs A) {
         int q, trow;
         if (REVEAL) {
             const int x = g * 16 + col;
-            q = x / A.G;
-            const int sl = x % A.G;
+            q = x >> lgG;
+            const int sl = x & (A.G - 1);
             q = q < A.nq ? q : 0;
             trow = A.pi[(size_t)q * A.T + A.lo + (sl < A.nb ? sl : 0)];
         } else {
@@ -197,7 +198,7 @@ void k_dense(DenseArgs A) {
 #pragma unroll
         for (int j = 0; j < Pack<NT>::NW; ++j) {
             const int g = tile0 + Pack<NT>::tile_of_row(j, lane >> 4);
-            int q = REVEAL ? (g * 16 + col) / A.G : g / TQ;
+            int q = REVEAL ? (g * 16 + col) >> lgG : g / TQ;
             q = q < A.nq ? q : 0;
             cscale[j] = A.qscale[q] * ds;
         }
@@ -212,7 +213,7 @@ void k_dense(DenseArgs A) {
 #pragma unroll
             for (int j = 0; j < P::NW; ++j) {
                 const int x = (tile0 + P::tile_of_row(j, lane >> 4)) * 16 + col;
-                const int q = x / A.G;
+                const int q = x >> lgG;
                 if (q < A.nq) {
                     const QueryCtl c = A.ctl[q];
                     if (c.active && c.mode == 0) qmask |= 1u << j;
@@ -240,7 +241,7 @@ void k_dense(DenseArgs A) {
 #pragma unroll
             for (int j = 0; j < P::NW; ++j) {
                 const int x = (tile0 + P::tile_of_row(j, row)) * 16 + col;
-                const int q = x / A.G, sl = x % A.G;
+                const int q = x >> lgG, sl = x & (A.G - 1);
                 float sb, m2b;
                 batch_stats(w[j], sl, A.nb, A.G, sb, m2b);
                 if (sl == 0 && q < A.nq && P::row_is_primary(row) && ((qmask >> j) & 1u))

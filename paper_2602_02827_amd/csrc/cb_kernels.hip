@@ -641,7 +641,7 @@ __device__ __forceinline__ void batch_stats_thread(const float (&c)[16], int nb,
     s = v[0];
     float dv[16];
     for (int i = 0; i < 16; ++i) {
-        const float d = (i < nb) ? (c[i] - v[i] / (float)nb) : 0.f;
+        const float d = (i < nb) ? (c[i] - div_count(v[i], nb)) : 0.f;
         dv[i] = d * d;
     }
     lanes_sum(dv, G);
