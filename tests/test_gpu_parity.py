@@ -446,6 +446,51 @@ def test_async_call_without_stats(B, S):
     assert torch.equal(r1["topk_ids"], r2["topk_ids"]) and torch.equal(r1["topk_scores"], r2["topk_scores"])
 
 
+def test_both_calls_can_be_captured_in_a_graph_and_replayed(B, S):
+    """Without statistics both entry points only enqueue kernels on the caller's stream (no
+    allocation, no memset, no read-back), so a caller may capture them in a HIP graph.  Every
+    replay, with eager work of the same library in between, must reproduce the eager result."""
+    w = S.config(1, device="cuda", scale=0.06, nq=8)            # N=3000
+    K = 5
+    ws = B.new_workspace(w.nq, w.T, w.d, w.N, w.total_tokens, "cuda")
+    d8, ds = B.colbandit_quantize_i8(w.docs)
+    outs = [{"topk_ids": torch.empty((w.nq, K), dtype=torch.int64, device="cuda"),
+             "topk_scores": torch.empty((w.nq, K), dtype=torch.float32, device="cuda")} for _ in range(3)]
+    scores = torch.empty((w.nq, w.N), dtype=torch.float32, device="cuda")
+
+    def run():
+        B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K, workspace=ws,
+                                out={**outs[0], "scores": scores})
+        B.colbandit_topk(w.Q, w.docs, w.offsets, K, 0.2, 0.01, 5, 3, workspace=ws, out=outs[1],
+                         want_stats=False)
+        B.colbandit_topk(w.Q, w.docs, w.offsets, K, 0.2, 0.01, 5, 3, workspace=ws, out=outs[2],
+                         want_stats=False, docs_i8=d8, docs_scale=ds)
+
+    run()
+    torch.cuda.synchronize()
+    ref = [(o["topk_ids"].clone(), o["topk_scores"].clone()) for o in outs]
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            run()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for o in outs:
+            o["topk_ids"].fill_(-7)
+            o["topk_scores"].fill_(0.0)
+        ws.fill_(0xAB)                                # the calls must not rely on workspace contents
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for o, (ids, sc) in zip(outs, ref):
+            assert torch.equal(o["topk_ids"], ids) and torch.equal(o["topk_scores"], sc)
+        other = B.colbandit_topk(w.Q, w.docs, w.offsets, 3, 0.5, 0.01, 2, 9, workspace=ws)   # eager, other knobs
+        torch.cuda.synchronize()
+        assert other["stats"][0]["rounds"] >= 1
+
+
 def test_validate_offsets(B, S):
     w = S.config(0, device="cuda")
     assert B.colbandit_validate_offsets(w.offsets, w.total_tokens) == 0
