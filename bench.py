@@ -48,8 +48,8 @@ def main():
     ap.add_argument("--cpu-sample-docs", type=int, default=60000)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding is described "
-              "in DESIGN.md, not built)", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding by query or by "
+              "document is a design note only, not built)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
