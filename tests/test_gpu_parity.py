@@ -509,7 +509,8 @@ def _host_values(x):
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("rows,d,nseg,permille", [(3001, 128, 1, 999), (64, 128, 4, 999), (32 * 9, 64, 9, 999),
-                                                   (1, 128, 1, 999), (500, 128, 1, 1000), (500, 128, 5, 500)])
+                                                   (1, 128, 1, 999), (500, 128, 1, 1000), (500, 128, 5, 500),
+                                                   (1200, 128, 2, 999), (1026, 100, 2, 900), (1001, 100, 1, 999)])
 def test_quantize_i8_codes_and_scales_match_oracle(B, oracle_mod, dtype, rows, d, nseg, permille):
     """Percentile clip and codes are integer results: exact equality with the oracle, which
     takes the deciding arithmetic in single precision as well."""
