@@ -22,6 +22,10 @@ _SRC = os.path.join(_HERE, "colbandit_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 
+_SELFTEST_SRC = os.path.join(_HERE, "selftest.c")
+_SELFTEST = os.path.join(_HERE, "selftest.bin")
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP across queries, no intrinsics)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
@@ -29,6 +33,18 @@ def build(force: bool = False) -> str:
                "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
+
+
+def build_selftest(sanitize: bool = True, out: str | None = None) -> str:
+    """Compile the oracle together with its driver selftest.c into an executable, by default
+    under AddressSanitizer + UndefinedBehaviorSanitizer (host code only)."""
+    out = out or _SELFTEST
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-Wall", "-Wextra", "-fno-omit-frame-pointer"]
+    if sanitize:
+        cmd += ["-fsanitize=address,undefined", "-fno-sanitize-recover=all"]
+    cmd += [_SRC, _SELFTEST_SRC, "-lm", "-o", out]
+    subprocess.run(cmd, check=True)
+    return out
 
 
 _lib = None

@@ -519,3 +519,15 @@ def test_quantisation_error_of_coarse_cells_is_bounded(oracle_mod):
     bound = np.abs(Q).sum(axis=1).max() * ed + np.abs(E).sum(axis=1).max() * eq + d * eq * ed
     assert np.max(np.abs(H8 - H)) <= bound
     assert np.max(np.abs(H8 - H)) > 0          # it is an approximation
+
+
+# ------------------------------------------------------------------ sanitizers (host code)
+def test_oracle_runs_clean_under_address_and_ub_sanitizers(oracle_mod, tmp_path):
+    """Every entry point of the oracle on exactly sized buffers, compiled with
+    -fsanitize=address,undefined: an out-of-bounds access, a leak or an undefined operation
+    inside the oracle aborts the driver."""
+    import subprocess
+    exe = oracle_mod.build_selftest(sanitize=True, out=str(tmp_path / "selftest_san"))
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "oracle selftest ok" in r.stdout
