@@ -422,6 +422,34 @@ def test_colbandit_small_candidate_sets(B, S, oracle_mod):
             assert torch.equal(res["topk_scores"], full["topk_scores"])
 
 
+@pytest.mark.parametrize("nq,T,d,N,K,M,Bsz,alpha,coarse", [
+    (2, 1, 128, 300, 3, 2, 4, 0.2, False),          # one query token: a single round, then exact
+    (2, 128, 128, 300, 5, 5, 16, 0.3, False),       # the largest T and B of this build
+    (1, 32, 128, 1100, 1024, 0, 4, 0.2, False),     # the largest K
+    (300, 16, 64, 500, 5, 5, 4, 0.2, False),        # many queries: several column groups, d=64
+    (3, 40, 64, 400, 4, 3, 5, 0.5, True),           # int8 rounds with d=64 and B not dividing T
+    (2, 100, 128, 300, 5, 5, 7, 1.0, True),         # int8 rounds, 7 tiles of query tokens
+    (4, 32, 128, 6, 5, 5, 4, 0.2, True),            # N <= K + M: no round at all
+])
+def test_colbandit_corner_shapes(B, S, oracle_mod, nq, T, d, N, K, M, Bsz, alpha, coarse):
+    rng = np.random.default_rng(N + T)
+    w = _custom(S, rng.integers(1, 70, N).tolist(), nq, T, d, "bf16", 59)
+    co = B.colbandit_quantize_i8(w.docs) if coarse else None
+    if nq > 16:                                     # keep the oracle leg to a few queries
+        full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K, want_cells=True)
+        res = B.colbandit_topk(w.Q, w.docs, w.offsets, K, alpha, 0.01, M, 5, B=Bsz, trace=True)
+        torch.cuda.synchronize()
+        for q in (0, 17, nq - 1):
+            Hq = full["cells"][q].cpu().numpy().astype(np.float64)
+            pi = B.colbandit_permutation(5, q, T)
+            div, orc = _compare_rounds(oracle_mod, res["trace"], q, Hq, K, M, Bsz, alpha, 0.01, pi)
+            assert div is None or div >= 0
+            got = res["topk_ids"][q]
+            assert torch.equal(res["topk_scores"][q], full["scores"][q][got])
+        return
+    _run_colbandit_case(B, oracle_mod, w, K, M, Bsz, alpha, seed=5, coarse=co, max_diverged=0.5)
+
+
 def test_explicit_permutation_and_determinism(B, S):
     w = S.config(1, device="cuda", scale=0.02, nq=4)
     pi = torch.tensor(np.stack([B.colbandit_permutation(77, q, w.T) for q in range(w.nq)]),
