@@ -275,6 +275,13 @@ def main():
         t0 = time.perf_counter()
         oracle.colbandit_batch(Qh, E, off, min(K, n_s), M, w.B, alpha, delta, pi)
         t_cb = time.perf_counter() - t0
+        # the same on ONE thread (one query; the oracle threads only across queries)
+        t0 = time.perf_counter()
+        oracle.full_batch(Qh[:1], E, off, min(K, n_s))
+        t_full1 = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.colbandit_batch(Qh[:1], E, off, min(K, n_s), M, w.B, alpha, delta, pi[:1])
+        t_cb1 = time.perf_counter() - t0
         scale = n_s / float(N)
         line["cpu_baseline"] = {
             "value": round(nq_s / (t_full + t_cb) * scale, 5), "unit": "queries/s",
@@ -282,7 +289,10 @@ def main():
             "sample": "%d queries x first %d documents of the same corpus, one thread per query; "
                       "%.1f s Full + %.1f s Col-Bandit measured, rate scaled by %d/%d to the full N"
                       % (nq_s, n_s, t_full, t_cb, n_s, N),
-            "full_s": round(t_full, 2), "colbandit_s": round(t_cb, 2)}
+            "full_s": round(t_full, 2), "colbandit_s": round(t_cb, 2),
+            "single_thread": {"value": round(1.0 / (t_full1 + t_cb1) * scale, 6), "unit": "queries/s",
+                              "full_s": round(t_full1, 2), "colbandit_s": round(t_cb1, 2),
+                              "colbandit_speedup_vs_full": round(t_full1 / t_cb1, 2)}}
     print(json.dumps(line))
 
 

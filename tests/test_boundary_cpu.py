@@ -186,3 +186,27 @@ def test_product_package_does_not_import_the_oracle():
                 src = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in src and "from oracle" not in src, f
                 assert "oracle/" not in src, f
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 and as C++ without any HIP or
+    torch type in sight, and every declaration must be usable from C."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text(
+        '#include <string.h>\n'
+        '#include "colbandit.h"\n'
+        "int main(void) {\n"
+        "    colbandit_opts o;\n"
+        "    colbandit_stats s;\n"
+        "    memset(&o, 0, sizeof o);\n"
+        "    memset(&s, 0, sizeof s);\n"
+        "    return (int)(colbandit_sizeof_opts() == sizeof(colbandit_opts)) - 1 +\n"
+        "           (int)(colbandit_sizeof_stats() == sizeof(colbandit_stats)) - 1;\n"
+        "}\n")
+    inc = os.path.join(ROOT, "include")
+    for cc, std in (("gcc", "-std=c99"), ("g++", "-std=c++11")):
+        r = subprocess.run([cc, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x",
+                            "c" if cc == "gcc" else "c++", "-I", inc, str(src)],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
