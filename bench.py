@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0
 # counter runs summarised in profiles/k_dense_C3_hbm_traffic.md (FETCH_SIZE + WRITE_SIZE, each
 # scaled by the same counter's reading for the 1 GiB calibration copy below).  Reported only
 # when the run is that workload.
-MEASURED_TRAFFIC_BYTES = {("C3-large-text-bf16", 128, 500000, 53040331): 15.41e9}
+MEASURED_TRAFFIC_BYTES = {("C3-large-text-bf16", 128, 500000, 53040331): 15.43e9}
 CALIBRATION_COPY_BYTES = 1 << 30
 
 
