@@ -6,7 +6,8 @@ and this module never imports the product package.
 
 All arithmetic lives in the C file; this module only marshals numpy arrays.
 Citations (paper): MaxSim cell / score Eq. (1)-(2), (4)-(5); top-K Eq. (3);
-bounds Eq. (7)-(8) and Appendix A; Algorithm 1 and its detailed listing.
+bounds Eq. (7)-(8) and Appendix A; Algorithm 1 and its detailed listing; the Doc-Uniform and
+Ball-carving baselines of the appendix "Compared Methods".
 """
 from __future__ import annotations
 
@@ -62,6 +63,11 @@ def _L():
         _lib.oracle_radius.argtypes = [ctypes.c_double, ctypes.c_int, ctypes.c_double,
                                        ctypes.c_int64, ctypes.c_double, ctypes.c_int]
         _lib.oracle_splitmix64_next.restype = ctypes.c_uint64
+        _lib.oracle_uniform_subset.restype = ctypes.c_uint64
+        _lib.oracle_uniform_subset.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_int64,
+                                               ctypes.c_int, ctypes.c_int]
+        _lib.oracle_round_bf16.restype = ctypes.c_float
+        _lib.oracle_round_bf16.argtypes = [ctypes.c_float]
     return _lib
 
 
@@ -267,6 +273,66 @@ def maxsim_cells_i8(Q8, sq, D8, sd, offsets):
                                        _p(H, ctypes.c_double), _p(Hint, ctypes.c_int32)),
            "maxsim_cells_i8")
     return H, Hint
+
+
+def uniform_subset(seed, q, i, T, m) -> int:
+    """Bit mask of the m query tokens Doc-Uniform reveals for (query q, document i)."""
+    return int(_L().oracle_uniform_subset(ctypes.c_uint64(seed & (2**64 - 1)), int(q), int(i),
+                                          int(T), int(m)))
+
+
+def doc_uniform_from_H(H, m, seed, query_index, K):
+    """Doc-Uniform over a MaxSim matrix H [N,T] (appendix "Compared Methods"): returns
+    (masks [N] uint64, S [N] float64 partial sums, top-K ids, top-K scores)."""
+    H = np.ascontiguousarray(H, dtype=np.float64)
+    N, T = H.shape
+    masks = np.empty(N, dtype=np.uint64)
+    S = np.empty(N, dtype=np.float64)
+    ids = np.empty(K, dtype=np.int64)
+    sc = np.empty(K, dtype=np.float64)
+    _check(_L().oracle_doc_uniform_from_H(_p(H, ctypes.c_double), ctypes.c_int64(N), T, int(m),
+                                          ctypes.c_uint64(seed & (2**64 - 1)),
+                                          ctypes.c_int64(query_index), int(K),
+                                          _p(masks, ctypes.c_uint64), _p(S, ctypes.c_double),
+                                          _p(ids, ctypes.c_int64), _p(sc, ctypes.c_double)),
+           "doc_uniform_from_H")
+    return masks, S, ids, sc
+
+
+def round_bf16(x: float) -> float:
+    return float(_L().oracle_round_bf16(ctypes.c_float(x)))
+
+
+def ball_carving_clusters(Q, tau, round_bf16=False):
+    """Greedy query clustering of Ball-carving: (k, labels [T] int32, C [T,d] float32 whose
+    first k rows are the centroids)."""
+    Q = _f32(Q)
+    T, d = Q.shape
+    labels = np.empty(T, dtype=np.int32)
+    C = np.empty((T, d), dtype=np.float32)
+    k = _check(_L().oracle_ball_carving_clusters(_p(Q, ctypes.c_float), T, d, ctypes.c_float(tau),
+                                                 int(bool(round_bf16)), _p(labels, ctypes.c_int32),
+                                                 _p(C, ctypes.c_float)), "ball_carving_clusters")
+    return k, labels, C
+
+
+def ball_carving(Q, E, offsets, tau, K, round_bf16=False):
+    """Ball-carving of one query: (k, labels, C, S [N] float64, top-K ids, top-K scores)."""
+    Q, E, offsets = _f32(Q), _f32(E), _i64(offsets)
+    T, d = Q.shape
+    N = offsets.shape[0] - 1
+    labels = np.empty(T, dtype=np.int32)
+    C = np.empty((T, d), dtype=np.float32)
+    S = np.empty(N, dtype=np.float64)
+    ids = np.empty(K, dtype=np.int64)
+    sc = np.empty(K, dtype=np.float64)
+    k = _check(_L().oracle_ball_carving(_p(Q, ctypes.c_float), T, d, ctypes.c_float(tau),
+                                        int(bool(round_bf16)), _p(E, ctypes.c_float),
+                                        _p(offsets, ctypes.c_int64), ctypes.c_int64(N), int(K),
+                                        _p(labels, ctypes.c_int32), _p(C, ctypes.c_float),
+                                        _p(S, ctypes.c_double), _p(ids, ctypes.c_int64),
+                                        _p(sc, ctypes.c_double)), "ball_carving")
+    return k, labels, C, S, ids, sc
 
 
 def colbandit_lazy(Q, E, offsets, K, M, B, alpha, delta, pi, a=-1.0, b=1.0):

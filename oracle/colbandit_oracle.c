@@ -21,6 +21,8 @@
  *     final top-K: Sec. 4.2, Algorithm 1 and its detailed listing in
  *     Appendix "Detailed Algorithm Listing" with the walkthrough and the
  *     complexity paragraph (cells touched).
+ *   - the two non-adaptive baselines, Doc-Uniform and Ball-carving: appendix
+ *     "Compared Methods" and its two algorithm boxes.
  *
  * Readings taken where the paper is silent (each is listed in the design
  * notes of the repository):
@@ -523,6 +525,185 @@ int oracle_maxsim_cells_i8(const int8_t *Q8, float sq, int T, int d, const int8_
         }
     }
     return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* non-adaptive baselines (appendix "Compared Methods")                 */
+/* ------------------------------------------------------------------ */
+
+/*
+ * Doc-Uniform, the static random reveal (appendix "Compared Methods", Doc-Uniform paragraph
+ * and its algorithm box): every document gets its own uniformly drawn subset R_i of m query
+ * tokens, without replacement, and is ranked by the sum of those m cells.
+ *
+ * The subset of (query q, document i) as a bit mask over [0,T).  Readings (the paper fixes
+ * only "uniformly, without replacement"): the draw is Floyd's subset sampling -- for
+ * j = T-m .. T-1 take t = next() mod (j+1) and insert t, or j if t is already in -- fed by a
+ * SplitMix64 stream of its own per (q, i): one SplitMix64 step from the query's state
+ * seed + (q+1)*0x9E3779B97F4A7C15 gives a query key, and the stream of document i starts at
+ * state key + (i+1)*0xD1B54A32D192ED03.  PARITY UNPINNED with respect to the authors'
+ * generator, as for the reveal permutation.
+ */
+uint64_t oracle_uniform_subset(uint64_t seed, int64_t q, int64_t i, int T, int m)
+{
+    if (T < 1 || T > 64 || m < 0 || m > T)
+        return 0;
+    uint64_t qs = seed + ((uint64_t)q + 1ULL) * 0x9E3779B97F4A7C15ULL;
+    uint64_t key = oracle_splitmix64_next(&qs);
+    uint64_t st = key + ((uint64_t)i + 1ULL) * 0xD1B54A32D192ED03ULL;
+    uint64_t mask = 0;
+    for (int j = T - m; j < T; ++j) {
+        int t = (int)(oracle_splitmix64_next(&st) % (uint64_t)(j + 1));
+        if ((mask >> t) & 1ULL)
+            mask |= 1ULL << j;
+        else
+            mask |= 1ULL << t;
+    }
+    return mask;
+}
+
+/*
+ * Doc-Uniform scores of one query over a given MaxSim matrix H (N x T):
+ * S~_i = sum over t in R_i of H[i][t], t ascending; then the top-K by (S~ desc, id asc).
+ * masks [N] and S [N] may be NULL; out_ids/out_scores may be NULL when K == 0.
+ */
+int oracle_doc_uniform_from_H(const double *H, int64_t N, int T, int m, uint64_t seed,
+                              int64_t query_index, int K, uint64_t *masks, double *S,
+                              int64_t *out_ids, double *out_scores)
+{
+    if (!H || N < 1 || T < 1 || T > 64 || m < 1 || m > T || K < 0 || K > N)
+        return ORACLE_ERR_ARG;
+    double *Sq = S ? S : (double *)malloc(sizeof(double) * (size_t)N);
+    if (!Sq)
+        return ORACLE_ERR_NOMEM;
+    for (int64_t i = 0; i < N; ++i) {
+        uint64_t R = oracle_uniform_subset(seed, query_index, i, T, m);
+        double s = 0.0;
+        for (int t = 0; t < T; ++t)
+            if ((R >> t) & 1ULL)
+                s += H[(size_t)i * T + t];
+        Sq[i] = s;
+        if (masks)
+            masks[i] = R;
+    }
+    if (K > 0 && out_ids)
+        oracle_topk(Sq, NULL, N, K, out_ids, out_scores);
+    if (!S)
+        free(Sq);
+    return ORACLE_OK;
+}
+
+/* Nearest-even rounding of a float to the bf16 grid (result widened back to float). */
+float oracle_round_bf16(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    if ((u & 0x7F800000u) != 0x7F800000u) {          /* finite */
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        u &= 0xFFFF0000u;
+    }
+    float y;
+    memcpy(&y, &u, 4);
+    return y;
+}
+
+/*
+ * Ball-carving, step 1 (appendix "Compared Methods", Ball-carving paragraph and its algorithm
+ * box): greedy clustering of the T query tokens.  The smallest remaining index is the pivot;
+ * its cluster takes every remaining token whose cosine with the pivot is >= tau; the cluster
+ * is replaced by the SUM of its (unnormalised) members; repeat until no token remains.
+ *
+ * labels [T]: cluster index of each token, clusters numbered in pivot order.
+ * C [T x d]: row c holds centroid c for c < k, zeros beyond.  Returns k (>= 1) or an error.
+ *
+ * Readings:
+ *   - a floating-point value decides a set here, so the test is fixed: with dot, |p|^2, |i|^2
+ *     plain double sums over k ascending, token i joins pivot p iff dot > 0 and
+ *     dot*dot >= ((tau*tau) * |p|^2) * |i|^2 in double -- the inequality cos >= tau (tau > 0)
+ *     freed of the square root and the division;
+ *   - the pivot always belongs to its own cluster, whatever rounding makes of its own cosine;
+ *   - a centroid is accumulated in single precision, members in ascending index, and, when
+ *     the embeddings are stored as bf16 (round_bf16 != 0), rounded to nearest-even bf16,
+ *     because the scoring kernel takes query rows in the storage type.
+ */
+int oracle_ball_carving_clusters(const float *Q, int T, int d, float tau, int round_bf16,
+                                 int32_t *labels, float *C)
+{
+    if (!Q || !labels || !C || T < 1 || d < 1 || !(tau > 0.0f) || !(tau <= 1.0f))
+        return ORACLE_ERR_ARG;
+    double *nn = (double *)malloc(sizeof(double) * (size_t)T);
+    if (!nn)
+        return ORACLE_ERR_NOMEM;
+    for (int t = 0; t < T; ++t) {
+        double s = 0.0;
+        for (int k = 0; k < d; ++k)
+            s += (double)Q[(size_t)t * d + k] * (double)Q[(size_t)t * d + k];
+        nn[t] = s;
+        labels[t] = -1;
+    }
+    memset(C, 0, sizeof(float) * (size_t)T * (size_t)d);
+    const double tau2 = (double)tau * (double)tau;
+    int k = 0;
+    for (int p = 0; p < T; ++p) {
+        if (labels[p] >= 0)
+            continue;                       /* p is the smallest remaining index: the pivot */
+        for (int i = p; i < T; ++i) {
+            if (labels[i] >= 0)
+                continue;
+            int in = (i == p);
+            if (!in) {
+                double dot = 0.0;
+                for (int c = 0; c < d; ++c)
+                    dot += (double)Q[(size_t)p * d + c] * (double)Q[(size_t)i * d + c];
+                in = dot > 0.0 && dot * dot >= (tau2 * nn[p]) * nn[i];
+            }
+            if (in) {
+                labels[i] = k;
+                for (int c = 0; c < d; ++c) {
+                    volatile float acc = C[(size_t)k * d + c] + Q[(size_t)i * d + c];
+                    C[(size_t)k * d + c] = acc;
+                }
+            }
+        }
+        if (round_bf16)
+            for (int c = 0; c < d; ++c)
+                C[(size_t)k * d + c] = oracle_round_bf16(C[(size_t)k * d + c]);
+        ++k;
+    }
+    free(nn);
+    return k;
+}
+
+/*
+ * Ball-carving, step 2: Score(doc) = sum over the k centroids of max_j <c, e_j>, then the
+ * top-K by (score desc, id asc).  S [N] may be NULL.  Returns k or an error.
+ */
+int oracle_ball_carving(const float *Q, int T, int d, float tau, int round_bf16, const float *E,
+                        const int64_t *off, int64_t N, int K, int32_t *labels, float *C,
+                        double *S, int64_t *out_ids, double *out_scores)
+{
+    if (!E || !off || N < 1 || K < 0 || K > N)
+        return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < N; ++i)
+        if (off[i + 1] <= off[i])
+            return ORACLE_ERR_EMPTY_DOC;
+    int k = oracle_ball_carving_clusters(Q, T, d, tau, round_bf16, labels, C);
+    if (k < 0)
+        return k;
+    double *Sq = S ? S : (double *)malloc(sizeof(double) * (size_t)N);
+    if (!Sq)
+        return ORACLE_ERR_NOMEM;
+    for (int64_t i = 0; i < N; ++i) {
+        double s = 0.0;
+        for (int c = 0; c < k; ++c)
+            s += oracle_cell(C, c, d, E, off, i);
+        Sq[i] = s;
+    }
+    if (K > 0 && out_ids)
+        oracle_topk(Sq, NULL, N, K, out_ids, out_scores);
+    if (!S)
+        free(Sq);
+    return k;
 }
 
 /* Col-Bandit that computes each revealed cell from the embeddings. */

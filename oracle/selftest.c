@@ -45,6 +45,16 @@ int oracle_colbandit_lazy(const float *Q, int T, int d, const float *E, const in
                           int64_t *final_ids, int64_t *n_final, int64_t *counts, double *tau,
                           int64_t *cells);
 int oracle_num_threads(void);
+uint64_t oracle_uniform_subset(uint64_t seed, int64_t q, int64_t i, int T, int m);
+int oracle_doc_uniform_from_H(const double *H, int64_t N, int T, int m, uint64_t seed,
+                              int64_t query_index, int K, uint64_t *masks, double *S,
+                              int64_t *out_ids, double *out_scores);
+float oracle_round_bf16(float x);
+int oracle_ball_carving_clusters(const float *Q, int T, int d, float tau, int round_bf16,
+                                 int32_t *labels, float *C);
+int oracle_ball_carving(const float *Q, int T, int d, float tau, int round_bf16, const float *E,
+                        const int64_t *off, int64_t N, int K, int32_t *labels, float *C,
+                        double *S, int64_t *out_ids, double *out_scores);
 int oracle_full_batch(const float *Q, int nq, int T, int d, const float *E, const int64_t *off,
                       int64_t N, int K, double *S, int64_t *out_ids, double *out_scores);
 int oracle_colbandit_batch(const float *Q, int nq, int T, int d, const float *E,
@@ -163,6 +173,27 @@ int main(void)
                                      final2, &n_final2, counts2, tau2, lcb, ucb, alive, cells2);
     CHECK(r4 >= 0 && n_final2 >= K);
     for (int k = 0; k < K; ++k) CHECK(fabs(out_sc2[k] - S[out_ids2[k]]) < 1e-12);   /* exact rescore */
+
+    /* the two non-adaptive baselines */
+    uint64_t um[N];
+    double us[N];
+    CHECK(oracle_doc_uniform_from_H(H, N, T, T, 5, 1, K, um, us, out_ids2, out_sc2) == 0);
+    for (int i = 0; i < N; ++i) CHECK(um[i] == (1u << T) - 1 && fabs(us[i] - S[i]) < 1e-12);
+    for (int k = 0; k < K; ++k) CHECK(out_ids2[k] == ids[k]);      /* every cell: exhaustive */
+    CHECK(oracle_doc_uniform_from_H(H, N, T, 3, 5, 1, K, um, NULL, out_ids2, out_sc2) == 0);
+    for (int i = 0; i < N; ++i) CHECK(__builtin_popcountll(um[i]) == 3 && um[i] < (1u << T));
+    CHECK(oracle_uniform_subset(5, 1, N - 1, T, 3) == um[N - 1]);
+    CHECK(oracle_round_bf16(1.0f) == 1.0f && oracle_round_bf16(1.00390625f) == 1.0f);
+    int32_t lab[T];
+    float *C = malloc(sizeof(float) * T * D);
+    CHECK(C);
+    int kc = oracle_ball_carving(Q, T, D, 1.0f, 0, E, off, N, K, lab, C, us, out_ids2, out_sc2);
+    CHECK(kc == T);                                     /* tau = 1: every token its own cluster */
+    for (int i = 0; i < N; ++i) CHECK(fabs(us[i] - S[i]) < 1e-12);
+    kc = oracle_ball_carving(Q, T, D, 0.05f, 1, E, off, N, K, lab, C, NULL, out_ids2, out_sc2);
+    CHECK(kc >= 1 && kc <= T && lab[0] == 0);
+    CHECK(oracle_ball_carving_clusters(Q, T, D, 0.5f, 0, lab, C) >= 1);
+    free(C);
 
     /* batch entry points (OpenMP) */
     CHECK(oracle_num_threads() >= 1);

@@ -521,6 +521,168 @@ def test_quantisation_error_of_coarse_cells_is_bounded(oracle_mod):
     assert np.max(np.abs(H8 - H)) > 0          # it is an approximation
 
 
+# ------------------------------------------------------------------ non-adaptive baselines
+def _popcount(x):
+    return bin(int(x)).count("1")
+
+
+def test_doc_uniform_subsets_have_the_stated_size_and_are_uniform(oracle_mod):
+    """Doc-Uniform's algorithm box: |R_i| = m, R_i a subset of [T], drawn uniformly without
+    replacement and independently per document.  Frequencies of single tokens (m/T) and of token
+    pairs (m(m-1)/(T(T-1))) over many documents pin the sampler; an off-by-one in the draw
+    (a token never or always chosen) or sampling with replacement fails them."""
+    T, m, n = 32, 4, 40000
+    masks = [oracle_mod.uniform_subset(7, 3, i, T, m) for i in range(n)]
+    assert all(_popcount(x) == m and x < (1 << T) for x in masks)
+    bits = np.array([[(x >> t) & 1 for t in range(T)] for x in masks], dtype=np.float64)
+    p1 = m / T
+    assert np.max(np.abs(bits.mean(axis=0) - p1)) < 5 * math.sqrt(p1 * (1 - p1) / n)
+    co = bits.T @ bits / n
+    p2 = m * (m - 1) / (T * (T - 1))
+    offd = co[~np.eye(T, dtype=bool)]
+    assert np.max(np.abs(offd - p2)) < 6 * math.sqrt(p2 * (1 - p2) / n)
+    # all C(3,2) subsets of a tiny case about equally often; the extremes m = T and m = 0
+    tiny = [oracle_mod.uniform_subset(1, 0, i, 3, 2) for i in range(30000)]
+    for sub in (0b011, 0b101, 0b110):
+        assert abs(tiny.count(sub) / 30000 - 1 / 3) < 0.02
+    assert oracle_mod.uniform_subset(1, 0, 5, 40, 40) == (1 << 40) - 1
+    assert oracle_mod.uniform_subset(1, 0, 5, 64, 64) == (1 << 64) - 1
+    assert oracle_mod.uniform_subset(1, 0, 5, 64, 0) == 0
+    # a stream of its own per document and per query, reproducible from the seed
+    assert len(set(masks[:2000])) > 1500
+    assert [oracle_mod.uniform_subset(7, 4, i, T, m) for i in range(50)] != masks[:50]
+    assert [oracle_mod.uniform_subset(8, 3, i, T, m) for i in range(50)] != masks[:50]
+    assert [oracle_mod.uniform_subset(7, 3, i, T, m) for i in range(50)] == masks[:50]
+
+
+def test_doc_uniform_scores_are_partial_row_sums_and_full_budget_is_exhaustive(oracle_mod):
+    """Doc-Uniform paragraph: the prediction ranks documents by the sum of their revealed
+    cells; at gamma = 1 every cell is revealed and the ranking is the exhaustive one (Eq. (3))."""
+    rng = np.random.default_rng(21)
+    N, T = 60, 12
+    H = rng.standard_normal((N, T))
+    masks, S, ids, sc = oracle_mod.doc_uniform_from_H(H, 5, 99, 2, 7)
+    for i in range(N):
+        assert masks[i] == oracle_mod.uniform_subset(99, 2, i, T, 5)
+        want = math.fsum(H[i, t] for t in range(T) if (int(masks[i]) >> t) & 1)
+        assert S[i] == pytest.approx(want, abs=1e-12)
+    order = sorted(range(N), key=lambda i: (-S[i], i))[:7]
+    assert list(ids) == order and np.array_equal(sc, S[order])
+    masks, S, ids, sc = oracle_mod.doc_uniform_from_H(H, T, 99, 2, 7)
+    assert np.allclose(S, H.sum(axis=1), atol=1e-12)
+    assert list(ids) == sorted(range(N), key=lambda i: (-H[i].sum(), i))[:7]
+    # ties go to the lower document index
+    Hc = np.ones((5, 4))
+    assert list(oracle_mod.doc_uniform_from_H(Hc, 2, 0, 0, 3)[2]) == [0, 1, 2]
+
+
+def test_round_bf16_matches_the_library_conversion(oracle_mod):
+    """Round-to-nearest-even onto the bf16 grid, against torch's float32 -> bfloat16
+    conversion, ties included."""
+    import torch
+    rng = np.random.default_rng(5)
+    xs = np.concatenate([rng.standard_normal(2000).astype(np.float32) * 7,
+                         np.array([1.00390625, 1.01171875, -1.00390625, 0.0, 3.0e38, 1e-40,
+                                   1.0 + 2**-8 + 2**-20], dtype=np.float32)])
+    want = torch.from_numpy(xs).to(torch.bfloat16).to(torch.float32).numpy()
+    got = np.array([oracle_mod.round_bf16(float(x)) for x in xs], dtype=np.float32)
+    assert np.array_equal(got, want)
+
+
+def _unit(deg):
+    return np.array([math.cos(math.radians(deg)), math.sin(math.radians(deg))])
+
+
+def test_ball_carving_hand_worked_clusters(oracle_mod):
+    """Ball-carving's algorithm box on six planar tokens at known angles with tau = cos 30deg:
+    the cluster is taken around the PIVOT (the smallest remaining index), not around the growing
+    centroid and not by chaining (50deg is within 30deg of 25deg but not of the pivot at 0deg);
+    the centroid is the sum of the UNNORMALISED members (token 1 has norm 3)."""
+    ang = [0.0, 25.0, 50.0, 20.0, 81.0, 52.0]
+    scale = [1.0, 3.0, 1.0, 1.0, 2.0, 0.5]
+    Q = np.array([s * _unit(a) for a, s in zip(ang, scale)], dtype=np.float32)
+    k, labels, C = oracle_mod.ball_carving_clusters(Q, math.cos(math.radians(30.0)))
+    assert k == 3 and list(labels) == [0, 0, 1, 0, 2, 1]
+    Qd = Q.astype(np.float64)
+    assert np.allclose(C[0], Qd[0] + Qd[1] + Qd[3], atol=1e-6)
+    assert np.allclose(C[1], Qd[2] + Qd[5], atol=1e-6)
+    assert np.allclose(C[2], Qd[4], atol=0)
+    assert np.all(C[3:] == 0)
+    # a looser threshold merges around the first pivot only what is within 60deg of it
+    k, labels, _ = oracle_mod.ball_carving_clusters(Q, 0.5)
+    assert k == 2 and list(labels) == [0, 0, 0, 0, 1, 0]
+    # opposite directions never merge, however small tau is
+    Qa = np.array([_unit(0), _unit(180), _unit(90), _unit(179)], dtype=np.float32)
+    k, labels, _ = oracle_mod.ball_carving_clusters(Qa, 1e-3)
+    assert k == 3 and list(labels) == [0, 1, 2, 1]
+
+
+def test_ball_carving_membership_against_normalise_then_dot(oracle_mod):
+    """The membership test is cos(pivot, token) >= tau.  An independent statement of the same
+    greedy rule with explicitly normalised tokens (numpy, double) must give the same clusters
+    on random queries for every tau of the paper's sweep (no cosine of these inputs lies within
+    1e-9 of a threshold, asserted)."""
+    rng = np.random.default_rng(77)
+    for trial in range(6):
+        T, d = 32, 16
+        base = rng.standard_normal((4, d))
+        Q = (base[rng.integers(0, 4, T)] + 0.45 * rng.standard_normal((T, d))).astype(np.float32)
+        Q *= rng.uniform(0.5, 2.0, (T, 1)).astype(np.float32)
+        Qn = Q.astype(np.float64) / np.linalg.norm(Q.astype(np.float64), axis=1, keepdims=True)
+        cos = Qn @ Qn.T
+        for tau in (0.4, 0.5, 0.6, 0.7, 0.8, 0.9):
+            tau32 = float(np.float32(tau))
+            assert np.min(np.abs(cos - tau32)) > 1e-9
+            remaining, want, kk = list(range(T)), [-1] * T, 0
+            while remaining:
+                p = remaining[0]
+                members = [i for i in remaining if i == p or cos[p, i] >= tau32]
+                for i in members:
+                    want[i] = kk
+                remaining = [i for i in remaining if i not in members]
+                kk += 1
+            k, labels, C = oracle_mod.ball_carving_clusters(Q, tau)
+            assert k == kk and list(labels) == want
+            for c in range(k):
+                assert np.allclose(C[c], Q[np.array(want) == c].astype(np.float64).sum(axis=0),
+                                   rtol=1e-5, atol=1e-5)
+
+
+def test_ball_carving_limits_and_score(oracle_mod):
+    """tau = 1 keeps every (distinct) token as its own cluster and recovers the exhaustive
+    score (Ball-carving paragraph); identical directions collapse into one centroid equal to
+    their sum; the score is one MaxSim term per centroid, checked by loops on a tiny ragged
+    corpus; bf16 storage rounds the centroid onto the bf16 grid."""
+    rng = np.random.default_rng(31)
+    Q, E, off = _ragged(rng, 9, 1, 6, 8, 5)
+    k, labels, C, S, ids, sc = oracle_mod.ball_carving(Q, E, off, 1.0, 3)
+    assert k == 5 and list(labels) == [0, 1, 2, 3, 4] and np.array_equal(C, Q)
+    H = np.array([[max(float(Q[t].astype(np.float64) @ E[j].astype(np.float64))
+                       for j in range(off[i], off[i + 1])) for t in range(5)] for i in range(9)])
+    assert np.allclose(S, H.sum(axis=1), atol=1e-12)
+    assert list(ids) == sorted(range(9), key=lambda i: (-S[i], i))[:3]
+    # scaled copies of one direction (powers of two: exact): one cluster at any tau
+    q0 = Q[0]
+    Qs = np.stack([q0, 2 * q0, 0.5 * q0, 4 * q0]).astype(np.float32)
+    k, labels, C, S, _, _ = oracle_mod.ball_carving(Qs, E, off, 1.0, 1)
+    assert k == 1 and list(labels) == [0, 0, 0, 0]
+    assert np.allclose(C[0], 7.5 * q0.astype(np.float64), rtol=1e-6)
+    assert np.allclose(S, 7.5 * H[:, 0], rtol=1e-6)
+    # a general tau: score = sum over centroids of the best token, written out
+    k, labels, C, S, _, _ = oracle_mod.ball_carving(Q, E, off, 0.1, 2)
+    for i in range(9):
+        want = math.fsum(max(float(C[c].astype(np.float64) @ E[j].astype(np.float64))
+                             for j in range(off[i], off[i + 1])) for c in range(k))
+        assert S[i] == pytest.approx(want, abs=1e-12)
+    # bf16 storage: centroids land on the bf16 grid and are the rounded single-precision sums
+    import torch
+    Qb = torch.from_numpy(Q).to(torch.bfloat16).to(torch.float32).numpy()
+    k, labels, Cb = oracle_mod.ball_carving_clusters(Qb, 0.1, round_bf16=True)
+    k2, labels2, Cf = oracle_mod.ball_carving_clusters(Qb, 0.1, round_bf16=False)
+    assert k == k2 and list(labels) == list(labels2)
+    assert np.array_equal(Cb, torch.from_numpy(Cf).to(torch.bfloat16).to(torch.float32).numpy())
+
+
 # ------------------------------------------------------------------ sanitizers (host code)
 def test_oracle_runs_clean_under_address_and_ub_sanitizers(oracle_mod, tmp_path):
     """Every entry point of the oracle on exactly sized buffers, compiled with
