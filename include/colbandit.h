@@ -236,6 +236,72 @@ int colbandit_topk(const void *Q, int n_queries, int T, int d, colbandit_dtype d
                    size_t workspace_bytes, void *stream);
 
 /*
+ * Doc-Uniform, the paper's static random-reveal baseline (appendix "Compared Methods",
+ * Doc-Uniform paragraph and its algorithm box): every (query, document) pair reveals its own
+ * uniformly drawn subset of `cells_per_doc` = ceil(gamma * T) query tokens, without
+ * replacement, and documents are ranked by the sum of the revealed cells.
+ *   cells_per_doc   1 .. T (the caller rounds gamma * T up; T <= 64)
+ *   seed            the subset of (query q, document i) is Floyd's subset sampling -- for
+ *                   j = T-m .. T-1: t = next() mod (j+1); insert t, or j if t is in already --
+ *                   on a SplitMix64 stream of its own: one SplitMix64 step from state
+ *                   seed + (q+1) * 0x9E3779B97F4A7C15 gives the query's key, the stream of
+ *                   document i starts at state key + (i+1) * 0xD1B54A32D192ED03
+ *   scores          DEVICE float [n_queries][N]: partial row sums, cells added in ascending
+ *                   token order in fp32; may be NULL when K > 0
+ *   masks           DEVICE uint64 [n_queries][N] or NULL: bit t set = token t revealed
+ *   K, topk_ids, topk_scores   as for colbandit_full_maxsim, ranking by the partial sums
+ * Subsets that differ per document leave no query column for a matrix tile to share, so the
+ * call computes the whole MaxSim matrix with the exhaustive kernel into the workspace
+ * (4 * n_queries * N * T bytes on top of colbandit_workspace_bytes) and then sums each row
+ * over its subset: on this machine the baseline costs a little more than Full-MaxSim whatever
+ * gamma is.  Fully asynchronous.  Other arguments as for colbandit_full_maxsim.
+ */
+size_t colbandit_doc_uniform_workspace_bytes(int n_queries, int T, int d, int64_t N,
+                                             int64_t total_tokens);
+int colbandit_doc_uniform(const void *Q, int n_queries, int T, int d, colbandit_dtype dt,
+                          const void *doc_tokens, const int64_t *doc_offsets, int64_t N,
+                          int64_t total_tokens, int K, int cells_per_doc, uint64_t seed,
+                          float *scores, uint64_t *masks, int64_t *topk_ids,
+                          float *topk_scores, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+/*
+ * Ball-carving, the paper's query-compression baseline (appendix "Compared Methods",
+ * Ball-carving paragraph and its algorithm box).  Step 1, per query: the smallest remaining
+ * token index is the pivot; its cluster takes every remaining token whose cosine with the
+ * pivot is >= tau; the cluster is replaced by the sum of its (unnormalised) members; repeat
+ * until no token remains (k clusters).  Step 2: Score(doc) = sum over the k centroids of
+ * max_j <c, e_j>; documents are ranked by it.  Coverage in the paper's sense is k / T.
+ *   tau          0 < tau <= 1; T <= 64
+ *   membership   token i joins pivot p iff dot > 0 and dot*dot >= ((tau*tau)*|p|^2)*|i|^2,
+ *                evaluated in double precision with sums over the components in ascending
+ *                order (cos >= tau without a square root or a division, so that the outcome
+ *                is reproducible bit for bit); the pivot always belongs to its own cluster
+ *   centroid     single-precision sum of the members in ascending index, then stored in
+ *                `dt` (bf16: round to nearest even) because the scoring kernels take query
+ *                rows in the storage type
+ *   n_clusters   DEVICE int32 [n_queries] or NULL: k of each query
+ *   labels       DEVICE int32 [n_queries][T] or NULL: cluster of each token (pivot order)
+ *   centroids    DEVICE `dt` [n_queries][T][d] or NULL: centroid c in row c, zero rows after
+ *   scores       DEVICE float [n_queries][N]; may be NULL when K > 0
+ *   K, topk_ids, topk_scores   as for colbandit_full_maxsim, ranking by Score
+ * bf16: the centroids of the whole batch are packed four to a group and scored by the
+ * corpus-streaming kernel, whose work follows the number of query columns, so the time
+ * follows sum_q 4*ceil(k_q/4); the call synchronises the stream once (it reads the number
+ * of groups back).  fp32: the zero-padded centroid matrix goes through the exhaustive
+ * gather kernel (a zero row's cell is 0).  Workspace: colbandit_ball_carving_workspace_bytes
+ * (for bf16 it holds 8 * n_queries * ceil(T/4) * N bytes of group sums).
+ */
+size_t colbandit_ball_carving_workspace_bytes(int n_queries, int T, int d, colbandit_dtype dt,
+                                              int64_t N, int64_t total_tokens);
+int colbandit_ball_carving(const void *Q, int n_queries, int T, int d, colbandit_dtype dt,
+                           const void *doc_tokens, const int64_t *doc_offsets, int64_t N,
+                           int64_t total_tokens, int K, float tau, int32_t *n_clusters,
+                           int32_t *labels, void *centroids, float *scores,
+                           int64_t *topk_ids, float *topk_scores, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/*
  * The reveal order used for query `query_index` under `seed` (Sec. 4.2: one uniform
  * permutation of [T] per query, fixed seed; the generator itself is this library's
  * choice): SplitMix64 started at seed + (query_index+1)*0x9E3779B97F4A7C15, then a

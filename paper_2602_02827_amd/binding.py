@@ -24,7 +24,8 @@ EXPORTS = [
     "colbandit_trace_bytes", "colbandit_permutation", "colbandit_radius_prefactor",
     "colbandit_validate_offsets", "colbandit_strerror", "colbandit_sizeof_opts",
     "colbandit_sizeof_stats", "colbandit_quantize_i8", "colbandit_quantize_workspace_bytes",
-    "colbandit_coarse_maxsim",
+    "colbandit_coarse_maxsim", "colbandit_doc_uniform", "colbandit_doc_uniform_workspace_bytes",
+    "colbandit_ball_carving", "colbandit_ball_carving_workspace_bytes",
 ]
 
 
@@ -88,6 +89,16 @@ def lib():
         L.colbandit_coarse_maxsim.restype = i
         L.colbandit_coarse_maxsim.argtypes = [vp, i, i, i, i, vp, vp, vp, i64, i64, i, vp, vp, vp, vp,
                                               vp, sz, vp]
+        L.colbandit_doc_uniform_workspace_bytes.restype = sz
+        L.colbandit_doc_uniform_workspace_bytes.argtypes = [i, i, i, i64, i64]
+        L.colbandit_doc_uniform.restype = i
+        L.colbandit_doc_uniform.argtypes = [vp, i, i, i, i, vp, vp, i64, i64, i, i, ctypes.c_uint64,
+                                            vp, vp, vp, vp, vp, sz, vp]
+        L.colbandit_ball_carving_workspace_bytes.restype = sz
+        L.colbandit_ball_carving_workspace_bytes.argtypes = [i, i, i, i, i64, i64]
+        L.colbandit_ball_carving.restype = i
+        L.colbandit_ball_carving.argtypes = [vp, i, i, i, i, vp, vp, i64, i64, i, f, vp, vp, vp, vp,
+                                             vp, vp, vp, sz, vp]
         L.colbandit_sizeof_opts.restype = sz
         L.colbandit_sizeof_opts.argtypes = []
         L.colbandit_sizeof_stats.restype = sz
@@ -227,6 +238,57 @@ def colbandit_coarse_maxsim(Q, docs_i8, docs_scale, offsets, permille=999, want_
     if rc:
         raise ColbanditError(rc, "colbandit_coarse_maxsim")
     return {"scores": scores, "cells": cells, "q_codes": qc, "q_scales": qs}
+
+
+def cells_per_doc(gamma: float, T: int) -> int:
+    """ceil(gamma * T) of Doc-Uniform, guarded against the binary representation of gamma
+    (0.1 * 30 must give 3, not 4)."""
+    import math
+    return max(1, min(T, math.ceil(round(float(gamma) * T, 6))))
+
+
+def colbandit_doc_uniform(Q, docs, offsets, K, m, seed=0, want_scores=True, want_masks=False,
+                          workspace=None):
+    """Doc-Uniform baseline with m cells per document.  Returns dict(scores, masks (int64 view
+    of the uint64 bit masks), topk_ids, topk_scores)."""
+    Q, nq, T, d, N, total = _shapes(Q, docs, offsets)
+    dev = docs.device
+    nb = int(lib().colbandit_doc_uniform_workspace_bytes(nq, T, d, N, total))
+    ws = workspace if workspace is not None else torch.empty(nb, dtype=torch.uint8, device=dev)
+    scores = torch.empty((nq, N), dtype=torch.float32, device=dev) if (want_scores or K == 0) else None
+    masks = torch.empty((nq, N), dtype=torch.int64, device=dev) if want_masks else None
+    ids = torch.empty((nq, K), dtype=torch.int64, device=dev) if K > 0 else None
+    sc = torch.empty((nq, K), dtype=torch.float32, device=dev) if K > 0 else None
+    rc = lib().colbandit_doc_uniform(_ptr(Q), nq, T, d, _dt(Q), _ptr(docs), _ptr(offsets), N, total,
+                                     int(K), int(m), ctypes.c_uint64(seed & (2**64 - 1)),
+                                     _ptr(scores), _ptr(masks), _ptr(ids), _ptr(sc), _ptr(ws),
+                                     ws.numel(), _stream())
+    if rc:
+        raise ColbanditError(rc, "colbandit_doc_uniform")
+    return {"scores": scores, "masks": masks, "topk_ids": ids, "topk_scores": sc}
+
+
+def colbandit_ball_carving(Q, docs, offsets, K, tau, want_scores=True, workspace=None):
+    """Ball-carving baseline at cosine threshold tau.  Returns dict(n_clusters [nq] int32,
+    labels [nq,T] int32, centroids [nq,T,d] (storage dtype), scores, topk_ids, topk_scores)."""
+    Q, nq, T, d, N, total = _shapes(Q, docs, offsets)
+    dev = docs.device
+    nb = int(lib().colbandit_ball_carving_workspace_bytes(nq, T, d, _dt(Q), N, total))
+    ws = workspace if workspace is not None else torch.empty(nb, dtype=torch.uint8, device=dev)
+    kq = torch.empty((nq,), dtype=torch.int32, device=dev)
+    labels = torch.empty((nq, T), dtype=torch.int32, device=dev)
+    cent = torch.empty((nq, T, d), dtype=Q.dtype, device=dev)
+    scores = torch.empty((nq, N), dtype=torch.float32, device=dev) if (want_scores or K == 0) else None
+    ids = torch.empty((nq, K), dtype=torch.int64, device=dev) if K > 0 else None
+    sc = torch.empty((nq, K), dtype=torch.float32, device=dev) if K > 0 else None
+    rc = lib().colbandit_ball_carving(_ptr(Q), nq, T, d, _dt(Q), _ptr(docs), _ptr(offsets), N, total,
+                                      int(K), ctypes.c_float(tau), _ptr(kq), _ptr(labels), _ptr(cent),
+                                      _ptr(scores), _ptr(ids), _ptr(sc), _ptr(ws), ws.numel(),
+                                      _stream())
+    if rc:
+        raise ColbanditError(rc, "colbandit_ball_carving")
+    return {"n_clusters": kq, "labels": labels, "centroids": cent, "scores": scores,
+            "topk_ids": ids, "topk_scores": sc}
 
 
 @dataclass

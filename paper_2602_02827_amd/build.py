@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcolbandit.so")
-SOURCES = ["cb_api.hip", "cb_kernels.hip", "cb_dense.hip", "cb_quant.hip"]
+SOURCES = ["cb_api.hip", "cb_kernels.hip", "cb_dense.hip", "cb_quant.hip", "cb_baselines.hip"]
 HEADERS = ["cb_device.h", "cb_launch.h", os.path.join("..", "..", "include", "colbandit.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-Xarch_device", "-fno-honor-nans", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms are kept off for the device code of this library

@@ -301,6 +301,167 @@ int colbandit_coarse_maxsim(const void* Q, int n_queries, int T, int d, colbandi
     return e == hipSuccess ? COLBANDIT_OK : COLBANDIT_ERR_HIP;
 }
 
+// ---- the two non-adaptive baselines (appendix "Compared Methods")
+
+namespace {
+struct UniformLayout { size_t base, cells, total; };
+UniformLayout uniform_layout(int nq, int T, int d, int64_t N, int64_t total_tokens) {
+    UniformLayout U{};
+    U.base = make_layout(nq, T, d, N, total_tokens).total;
+    U.cells = U.base;
+    U.total = U.cells + align_up(4 * (size_t)nq * (size_t)N * (size_t)T);
+    return U;
+}
+struct BallLayout { size_t base, Cz, kq, labels, goff, Qg, ident, part, total; int TG; };
+BallLayout ball_layout(int nq, int T, int d, int dt, int64_t N, int64_t total_tokens) {
+    BallLayout B{};
+    size_t o = make_layout(nq, T, d, N, total_tokens).total;
+    B.base = o;
+    auto take = [&](size_t bytes) {
+        const size_t at = o;
+        o = align_up(o + bytes);
+        return at;
+    };
+    const size_t elem = dt == COLBANDIT_BF16 ? 2 : 4;
+    B.TG = (T + 3) / 4;
+    B.Cz = take(elem * (size_t)nq * T * d);
+    B.kq = take(4 * (size_t)nq);
+    B.labels = take(4 * (size_t)nq * T);
+    B.goff = take(4 * ((size_t)nq + 1));
+    if (dt == COLBANDIT_BF16) {
+        B.Qg = take(2 * (size_t)nq * B.TG * 4 * d);
+        B.ident = take(4 * (size_t)nq * B.TG * 4);
+        B.part = take(8 * (size_t)nq * B.TG * (size_t)N);
+    }
+    B.total = o;
+    return B;
+}
+}  // namespace
+
+size_t colbandit_doc_uniform_workspace_bytes(int n_queries, int T, int d, int64_t N,
+                                             int64_t total_tokens) {
+    if (n_queries < 1 || T < 1 || N < 1 || total_tokens < N) return 0;
+    return uniform_layout(n_queries, T, d, N, total_tokens).total;
+}
+
+int colbandit_doc_uniform(const void* Q, int n_queries, int T, int d, colbandit_dtype dt,
+                          const void* doc_tokens, const int64_t* doc_offsets, int64_t N,
+                          int64_t total_tokens, int K, int cells_per_doc, uint64_t seed,
+                          float* scores, uint64_t* masks, int64_t* topk_ids, float* topk_scores,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_shapes(Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens);
+    if (rc) return rc;
+    if (K < 0 || K > N) return COLBANDIT_ERR_SHAPE;
+    if (K > COLBANDIT_MAX_K || T > 64) return COLBANDIT_ERR_UNSUPPORTED;
+    if (cells_per_doc < 1 || cells_per_doc > T) return COLBANDIT_ERR_KNOB;
+    if (K == 0 && !scores) return COLBANDIT_ERR_NULL;
+    if (K > 0 && (!topk_ids || !topk_scores)) return COLBANDIT_ERR_NULL;
+    if ((uintptr_t)masks & 7) return COLBANDIT_ERR_ALIGNMENT;
+    const UniformLayout U = uniform_layout(n_queries, T, d, N, total_tokens);
+    rc = check_workspace(workspace, workspace_bytes, U.total);
+    if (rc) return rc;
+    const Work W = carve(workspace, make_layout(n_queries, T, d, N, total_tokens));
+    const Problem P{Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens};
+    hipStream_t st = (hipStream_t)stream;
+    float* cells = (float*)((char*)workspace + U.cells);
+    float* out = scores ? scores : W.scores;
+    // the whole MaxSim matrix (exhaustive row sums go to a scratch array), then the subset sums
+    hipError_t e = hipSuccess;
+    if (dense_supported(P, nullptr)) {
+        int n_chunks = 0;
+        e = launch_dense_prepare(P, W, kChunkTokens, &n_chunks, st);
+        if (e == hipSuccess)
+            e = launch_dense_score(P, W, kChunkTokens, n_chunks, W.rescored, cells, nullptr, st);
+    } else {
+        e = launch_gather_score(P, W, false, W.rescored, cells, false, st);
+    }
+    if (e == hipSuccess)
+        e = launch_uniform_score(cells, n_queries, N, T, cells_per_doc, seed, out, masks, st);
+    if (e == hipSuccess && K > 0) e = launch_topk(P, W, false, out, K, topk_ids, topk_scores, st);
+    return e == hipSuccess ? COLBANDIT_OK : COLBANDIT_ERR_HIP;
+}
+
+size_t colbandit_ball_carving_workspace_bytes(int n_queries, int T, int d, colbandit_dtype dt,
+                                              int64_t N, int64_t total_tokens) {
+    if (n_queries < 1 || T < 1 || N < 1 || total_tokens < N) return 0;
+    if (dt != COLBANDIT_F32 && dt != COLBANDIT_BF16) return 0;
+    return ball_layout(n_queries, T, d, (int)dt, N, total_tokens).total;
+}
+
+int colbandit_ball_carving(const void* Q, int n_queries, int T, int d, colbandit_dtype dt,
+                           const void* doc_tokens, const int64_t* doc_offsets, int64_t N,
+                           int64_t total_tokens, int K, float tau, int32_t* n_clusters,
+                           int32_t* labels, void* centroids, float* scores, int64_t* topk_ids,
+                           float* topk_scores, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    int rc = check_shapes(Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens);
+    if (rc) return rc;
+    if (K < 0 || K > N) return COLBANDIT_ERR_SHAPE;
+    if (K > COLBANDIT_MAX_K || T > 64) return COLBANDIT_ERR_UNSUPPORTED;
+    if (!(tau > 0.f) || !(tau <= 1.f)) return COLBANDIT_ERR_KNOB;
+    if (K == 0 && !scores) return COLBANDIT_ERR_NULL;
+    if (K > 0 && (!topk_ids || !topk_scores)) return COLBANDIT_ERR_NULL;
+    if (((uintptr_t)n_clusters & 3) || ((uintptr_t)labels & 3) || ((uintptr_t)centroids & 15))
+        return COLBANDIT_ERR_ALIGNMENT;
+    const BallLayout B = ball_layout(n_queries, T, d, (int)dt, N, total_tokens);
+    rc = check_workspace(workspace, workspace_bytes, B.total);
+    if (rc) return rc;
+    const Work W = carve(workspace, make_layout(n_queries, T, d, N, total_tokens));
+    const Problem P{Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens};
+    hipStream_t st = (hipStream_t)stream;
+    char* b = (char*)workspace;
+    void* Cz = b + B.Cz;
+    int32_t* kq = (int32_t*)(b + B.kq);
+    int32_t* lab = (int32_t*)(b + B.labels);
+    int32_t* goff = (int32_t*)(b + B.goff);
+    float* out = scores ? scores : W.scores;
+    const size_t elem = dt == COLBANDIT_BF16 ? 2 : 4;
+
+    hipError_t e = launch_ball_carve(P, tau, Cz, lab, kq, st);
+    if (e == hipSuccess && dt == COLBANDIT_BF16 && dense_supported(P, nullptr)) {
+        // centroids of the batch, four to a group, through the corpus-streaming reveal kernel:
+        // its work follows the number of query columns, i.e. the number of centroids
+        void* Qg = b + B.Qg;
+        int32_t* ident = (int32_t*)(b + B.ident);
+        float2* part = (float2*)(b + B.part);
+        e = launch_ball_groups(P, Cz, kq, goff, Qg, ident, st);
+        int32_t ng = 0;
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(&ng, goff + n_queries, sizeof(int32_t), hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e == hipSuccess && (ng < n_queries || (int64_t)ng > (int64_t)n_queries * B.TG))
+            e = hipErrorUnknown;
+        int n_chunks = 0;
+        if (e == hipSuccess) e = launch_dense_prepare(P, W, kChunkTokens, &n_chunks, st);
+        if (e == hipSuccess) {
+            const Problem P2{Qg, ng, 4, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens};
+            Work W2 = W;
+            W2.pi = ident;
+            W2.stat = part;
+            RevealRound rr{};
+            rr.r = 1;
+            rr.lo = 0;
+            rr.nb = 4;
+            rr.n = 4;
+            rr.dense_thr = ~0ull;
+            e = launch_dense_reveal(P2, W2, kChunkTokens, n_chunks, rr, 4, nullptr, st);
+        }
+        if (e == hipSuccess) e = launch_ball_reduce((const float*)part, 2, goff, n_queries, N, out, st);
+    } else if (e == hipSuccess) {
+        // fp32: exhaustive scoring of the zero-padded centroid matrix (a zero row's cell is 0)
+        const Problem P3{Cz, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens};
+        e = launch_gather_score(P3, W, false, out, nullptr, false, st);
+    }
+    if (e == hipSuccess && n_clusters)
+        e = hipMemcpyAsync(n_clusters, kq, 4 * (size_t)n_queries, hipMemcpyDeviceToDevice, st);
+    if (e == hipSuccess && labels)
+        e = hipMemcpyAsync(labels, lab, 4 * (size_t)n_queries * T, hipMemcpyDeviceToDevice, st);
+    if (e == hipSuccess && centroids)
+        e = hipMemcpyAsync(centroids, Cz, elem * (size_t)n_queries * T * d, hipMemcpyDeviceToDevice, st);
+    if (e == hipSuccess && K > 0) e = launch_topk(P, W, false, out, K, topk_ids, topk_scores, st);
+    return e == hipSuccess ? COLBANDIT_OK : COLBANDIT_ERR_HIP;
+}
+
 size_t colbandit_sizeof_opts(void) { return sizeof(colbandit_opts); }
 size_t colbandit_sizeof_stats(void) { return sizeof(colbandit_stats); }
 

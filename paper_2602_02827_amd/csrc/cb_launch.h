@@ -130,6 +130,23 @@ hipError_t launch_quantize_i8(const void* x, int dt, int64_t n_segments, int64_t
                               int permille, int8_t* codes, float* scales, void* scratch,
                               hipStream_t st);
 
+// Doc-Uniform (appendix "Compared Methods"): scores[q][i] = sum of cells[q][i][t] over the
+// seeded random subset of m tokens of (q, i); masks (nullable) receives the subsets.
+hipError_t launch_uniform_score(const float* cells, int nq, int64_t N, int T, int m, uint64_t seed,
+                                float* scores, uint64_t* masks, hipStream_t st);
+// Ball-carving (same appendix): greedy clustering of each query's tokens at cosine threshold
+// tau.  Cz [nq][T][d] (storage type): centroid c of query q in row c, zero rows past the last;
+// labels [nq][T] (nullable): cluster of each token; kq [nq]: clusters per query.
+hipError_t launch_ball_carve(const Problem& P, float tau, void* Cz, int32_t* labels, int32_t* kq,
+                             hipStream_t st);
+// bf16: packs the centroids four to a group.  goff [nq+1]: first group of each query and the
+// total; Qg [total groups][4][d]; ident [total groups][4] = 0,1,2,3.
+hipError_t launch_ball_groups(const Problem& P, const void* Cz, const int32_t* kq, int32_t* goff,
+                              void* Qg, int32_t* ident, hipStream_t st);
+// scores[q][i] = sum over the groups of q, ascending, of part[(g * N + i) * stride].
+hipError_t launch_ball_reduce(const float* part, int stride, const int32_t* goff, int nq, int64_t N,
+                              float* scores, hipStream_t st);
+
 hipError_t launch_validate_offsets(const int64_t* off, int64_t N, int64_t total, int* flag,
                                    hipStream_t st);
 

@@ -148,6 +148,54 @@ def test_coarse_pass_argument_errors(B):
     assert coarse(wsb=1024) == -5
 
 
+def test_baseline_argument_errors(B):
+    """colbandit_doc_uniform / colbandit_ball_carving reject bad arguments before any launch."""
+    L = B.lib()
+
+    def uni(**kw):
+        a = dict(Q=0x1000, nq=1, T=32, d=128, dt=1, docs=0x2000, off=0x3000, N=10, total=400, K=0,
+                 m=4, seed=0, scores=0x4000, masks=None, ids=None, sc=None, ws=0x10000, wsb=1 << 40)
+        a.update(kw)
+        return L.colbandit_doc_uniform(a["Q"], a["nq"], a["T"], a["d"], a["dt"], a["docs"], a["off"],
+                                       a["N"], a["total"], a["K"], a["m"], a["seed"], a["scores"],
+                                       a["masks"], a["ids"], a["sc"], a["ws"], a["wsb"], None)
+    assert uni(Q=None) == -1 and uni(docs=None) == -1 and uni(off=None) == -1
+    assert uni(scores=None) == -1                       # K == 0 needs the scores
+    assert uni(K=3) == -1                               # K > 0 needs the top-K outputs
+    assert uni(K=11) == -2 and uni(N=0) == -2 and uni(dt=7) == -2
+    assert uni(m=0) == -3 and uni(m=33) == -3
+    assert uni(T=65, m=4) == -4 and uni(d=96) == -4
+    assert uni(masks=0x5004) == -6 and uni(Q=0x1008) == -6
+    assert uni(ws=None) == -1 and uni(wsb=1024) == -5
+    assert L.colbandit_doc_uniform_workspace_bytes(0, 32, 128, 10, 400) == 0
+    base = B.colbandit_workspace_bytes(2, 32, 128, 1000, 48000)
+    wu = L.colbandit_doc_uniform_workspace_bytes(2, 32, 128, 1000, 48000)
+    assert wu >= base + 4 * 2 * 1000 * 32 and wu % 256 == 0
+
+    def ball(**kw):
+        a = dict(Q=0x1000, nq=1, T=32, d=128, dt=1, docs=0x2000, off=0x3000, N=10, total=400, K=0,
+                 tau=0.7, kq=None, labels=None, cent=None, scores=0x4000, ids=None, sc=None,
+                 ws=0x10000, wsb=1 << 40)
+        a.update(kw)
+        return L.colbandit_ball_carving(a["Q"], a["nq"], a["T"], a["d"], a["dt"], a["docs"], a["off"],
+                                        a["N"], a["total"], a["K"], a["tau"], a["kq"], a["labels"],
+                                        a["cent"], a["scores"], a["ids"], a["sc"], a["ws"], a["wsb"],
+                                        None)
+    assert ball(Q=None) == -1 and ball(docs=None) == -1 and ball(scores=None) == -1 and ball(K=2) == -1
+    assert ball(K=11) == -2 and ball(nq=0) == -2
+    assert ball(tau=0.0) == -3 and ball(tau=-0.5) == -3 and ball(tau=1.5) == -3
+    assert ball(tau=float("nan")) == -3
+    assert ball(T=65) == -4
+    assert ball(kq=0x5002) == -6 and ball(labels=0x5001) == -6 and ball(cent=0x5008) == -6
+    assert ball(ws=None) == -1 and ball(wsb=1024) == -5
+    wb16 = L.colbandit_ball_carving_workspace_bytes(2, 32, 128, 1, 1000, 48000)
+    wb32 = L.colbandit_ball_carving_workspace_bytes(2, 32, 128, 0, 1000, 48000)
+    assert wb16 >= base + 8 * 2 * 8 * 1000 and wb32 >= base + 4 * 2 * 32 * 128
+    assert L.colbandit_ball_carving_workspace_bytes(2, 32, 128, 5, 1000, 48000) == 0
+    assert B.cells_per_doc(0.1, 30) == 3 and B.cells_per_doc(0.05, 32) == 2
+    assert B.cells_per_doc(1.0, 32) == 32 and B.cells_per_doc(0.001, 32) == 1
+
+
 def test_workspace_and_trace_sizes(B):
     assert B.colbandit_workspace_bytes(0, 32, 128, 10, 100) == 0
     assert B.colbandit_workspace_bytes(1, 32, 128, 10, 5) == 0

@@ -622,6 +622,107 @@ def test_colbandit_on_int8_codes_all_reveal_paths_agree(B, S, oracle_mod):
     _run_colbandit_case(B, oracle_mod, w32, 5, 5, 4, 0.3, coarse=(d8, ds))
 
 
+# ------------------------------------------------------------------ non-adaptive baselines
+def _clustered_queries(w, S, n_dir, noise, seed):
+    """Replaces the workload's queries by tokens scattered around n_dir directions with random
+    norms, so that a sweep of the cosine threshold gives anything from one cluster to T."""
+    g = torch.Generator(device="cpu"); g.manual_seed(seed)
+    nq, T, d = w.Q.shape
+    base = torch.randn((nq, n_dir, d), generator=g)
+    base = base / base.norm(dim=2, keepdim=True)
+    pick = torch.randint(0, n_dir, (nq, T), generator=g)
+    Q = torch.gather(base, 1, pick[..., None].expand(nq, T, d)) + noise * torch.randn((nq, T, d), generator=g) / d ** 0.5
+    Q = Q * (0.5 + 1.5 * torch.rand((nq, T, 1), generator=g))
+    w.Q = Q.to(w.Q.dtype).cuda()
+    return w
+
+
+@pytest.mark.parametrize("dtype,nq,T,d,m", [("bf16", 3, 32, 128, 4), ("bf16", 20, 32, 128, 13),
+                                            ("bf16", 2, 64, 128, 64), ("bf16", 5, 7, 64, 1),
+                                            ("bf16", 4, 30, 128, 30), ("f32", 2, 32, 128, 8),
+                                            ("f32", 3, 24, 64, 5)])
+def test_doc_uniform_masks_scores_and_topk_match_oracle(B, S, oracle_mod, dtype, nq, T, d, m):
+    """Doc-Uniform (appendix "Compared Methods"): the per-document token subsets are the oracle's
+    bit for bit (same counter-based generator, implemented on each side), the partial row sums
+    agree within the score tolerance, the top-K follows them."""
+    rng = np.random.default_rng(T * 100 + m)
+    lengths = [1, 16, 17, 63, 65, 300, 1] + rng.integers(1, 120, 260).tolist()
+    w = _custom(S, lengths, nq, T, d, dtype, 41)
+    seed, K = 1234567, 6
+    r = B.colbandit_doc_uniform(w.Q, w.docs, w.offsets, K, m, seed=seed, want_masks=True)
+    torch.cuda.synchronize()
+    H, _ = _oracle_scores(oracle_mod, w)
+    masks = r["masks"].cpu().numpy().view(np.uint64)
+    got = r["scores"].cpu().numpy()
+    tol = TOL[dtype]
+    for q in range(nq):
+        mo, So, _, _ = oracle_mod.doc_uniform_from_H(H[q], m, seed, q, K)
+        np.testing.assert_array_equal(masks[q], mo)
+        np.testing.assert_allclose(got[q], So, rtol=tol, atol=tol)
+        _check_topk(r["topk_ids"][q].cpu().numpy(), r["topk_scores"][q].cpu().numpy(), So, K, tol)
+    if m == T:      # every cell revealed: the exhaustive scores (other summation order)
+        full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=0)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(got, full["scores"].cpu().numpy(), rtol=1e-5, atol=1e-5)
+    # top-K only (scores kept in the workspace) gives the same ranking
+    r2 = B.colbandit_doc_uniform(w.Q, w.docs, w.offsets, K, m, seed=seed, want_scores=False)
+    torch.cuda.synchronize()
+    assert torch.equal(r2["topk_ids"], r["topk_ids"]) and torch.equal(r2["topk_scores"], r["topk_scores"])
+
+
+@pytest.mark.parametrize("dtype,nq,T,d,tau", [("bf16", 3, 32, 128, 0.7), ("bf16", 40, 32, 128, 0.9),
+                                              ("bf16", 6, 32, 128, 0.4), ("bf16", 2, 64, 128, 0.8),
+                                              ("bf16", 5, 7, 64, 0.6), ("bf16", 4, 30, 128, 1.0),
+                                              ("bf16", 1, 1, 128, 0.5), ("f32", 2, 32, 128, 0.7),
+                                              ("f32", 3, 24, 64, 0.5)])
+def test_ball_carving_clusters_centroids_scores_match_oracle(B, S, oracle_mod, dtype, nq, T, d, tau):
+    """Ball-carving (appendix "Compared Methods"): cluster labels and cluster counts are exact
+    (the membership test is taken in the same double-precision form on both sides), the
+    centroids are the oracle's bit for bit, scores and top-K agree within the score tolerance."""
+    rng = np.random.default_rng(T * 10 + nq)
+    lengths = [1, 16, 17, 63, 65, 300, 1] + rng.integers(1, 120, 260).tolist()
+    w = _clustered_queries(_custom(S, lengths, nq, T, d, dtype, 43), S, 4, 0.6, 5)
+    K = 6
+    r = B.colbandit_ball_carving(w.Q, w.docs, w.offsets, K, tau)
+    torch.cuda.synchronize()
+    E, off = w.host_docs()
+    Qh = w.host_queries()
+    tol = TOL[dtype]
+    ks = []
+    for q in range(nq):
+        k, labels, C, So, _, _ = oracle_mod.ball_carving(Qh[q], E, off, tau, K, round_bf16=(dtype == "bf16"))
+        ks.append(k)
+        assert int(r["n_clusters"][q]) == k
+        np.testing.assert_array_equal(r["labels"][q].cpu().numpy(), labels)
+        np.testing.assert_array_equal(r["centroids"][q].float().cpu().numpy(), C)
+        scale = max(1.0, float(np.abs(So).max()))
+        np.testing.assert_allclose(r["scores"][q].cpu().numpy(), So, rtol=tol, atol=tol * scale)
+        _check_topk(r["topk_ids"][q].cpu().numpy(), r["topk_scores"][q].cpu().numpy(), So, K, tol)
+    if tau == 1.0:
+        assert ks == [T] * nq
+        full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=0)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(r["scores"].cpu().numpy(), full["scores"].cpu().numpy(),
+                                   rtol=1e-4, atol=1e-4)
+    if T >= 24 and tau <= 0.7:
+        assert min(ks) < T                               # the sweep point does compress
+
+
+def test_ball_carving_identical_tokens_collapse_to_one_centroid(B, S, oracle_mod):
+    w = _custom(S, np.random.default_rng(3).integers(1, 90, 150).tolist(), 2, 32, 128, "bf16", 47)
+    w.Q = (w.Q[:, :1, :].float() * torch.tensor([1.0, 2.0, 0.5, 4.0] * 8, device="cuda")[None, :, None]) \
+        .to(torch.bfloat16).contiguous()
+    r = B.colbandit_ball_carving(w.Q, w.docs, w.offsets, 3, 1.0)
+    torch.cuda.synchronize()
+    assert r["n_clusters"].tolist() == [1, 1] and int(r["labels"].abs().sum()) == 0
+    E, off = w.host_docs()
+    for q in range(2):
+        k, _, C, So, _, _ = oracle_mod.ball_carving(w.host_queries()[q], E, off, 1.0, 3, round_bf16=True)
+        assert k == 1
+        np.testing.assert_array_equal(r["centroids"][q].float().cpu().numpy(), C)
+        np.testing.assert_allclose(r["scores"][q].cpu().numpy(), So, rtol=TOL["bf16"], atol=1e-3)
+
+
 # ------------------------------------------------------------------ full size, bench launch configuration
 @pytest.fixture(scope="module")
 def big(B, S):
@@ -713,3 +814,43 @@ def test_full_size_colbandit_rounds_and_survivor_scores(B, oracle_mod, big):
             np.testing.assert_allclose(fin[np.argsort(-fin, kind="stable")][:K],
                                        np.sort(res["topk_scores"][q].cpu().numpy().astype(np.float64))[::-1],
                                        rtol=1e-5)
+
+
+def test_full_size_baselines_on_sampled_documents(B, oracle_mod, big):
+    """Doc-Uniform and Ball-carving at the benchmark's size: subsets, clusters and centroids exact
+    for sampled queries; scores of sampled documents against the oracle."""
+    w, ws, full, K = big
+    rng = np.random.default_rng(77)
+    qs = [0, 64, 127]
+    docs = np.unique(np.concatenate([rng.integers(0, w.N, 30), [0, w.N - 1]]))
+    E, off = w.host_docs(docs.tolist())
+    Qh = w.host_queries(qs)
+    dsel = torch.as_tensor(docs, device="cuda")
+    print("full-size Doc-Uniform ...", flush=True)
+    m, seed = 8, 99
+    ru = B.colbandit_doc_uniform(w.Q, w.docs, w.offsets, K, m, seed=seed, want_masks=True)
+    torch.cuda.synchronize()
+    for j, q in enumerate(qs):
+        H = oracle_mod.maxsim_cells(Qh[j], E, off)
+        masks = ru["masks"][q][dsel].cpu().numpy().view(np.uint64)
+        for n, i in enumerate(docs.tolist()):
+            R = oracle_mod.uniform_subset(seed, q, i, w.T, m)
+            assert int(masks[n]) == R
+            want = sum(H[n, t] for t in range(w.T) if (R >> t) & 1)
+            assert float(ru["scores"][q, i]) == pytest.approx(want, rel=TOL["bf16"], abs=1e-4)
+        sc = ru["scores"][q].cpu().numpy()
+        np.testing.assert_array_equal(ru["topk_ids"][q].cpu().numpy(), np.lexsort((np.arange(w.N), -sc))[:K])
+    del ru
+    print("full-size Ball-carving ...", flush=True)
+    tau = 0.7
+    rb = B.colbandit_ball_carving(w.Q, w.docs, w.offsets, K, tau)
+    torch.cuda.synchronize()
+    for j, q in enumerate(qs):
+        k, labels, C, So, _, _ = oracle_mod.ball_carving(Qh[j], E, off, tau, 1, round_bf16=True)
+        assert int(rb["n_clusters"][q]) == k
+        np.testing.assert_array_equal(rb["labels"][q].cpu().numpy(), labels)
+        np.testing.assert_array_equal(rb["centroids"][q].float().cpu().numpy(), C)
+        got = rb["scores"][q][dsel].cpu().numpy()
+        np.testing.assert_allclose(got, So, rtol=TOL["bf16"], atol=1e-3)
+        sc = rb["scores"][q].cpu().numpy()
+        np.testing.assert_array_equal(rb["topk_ids"][q].cpu().numpy(), np.lexsort((np.arange(w.N), -sc))[:K])
