@@ -242,8 +242,8 @@ int colbandit_topk(const void *Q, int n_queries, int T, int d, colbandit_dtype d
  * replacement, and documents are ranked by the sum of the revealed cells.
  *   cells_per_doc   1 .. T (the caller rounds gamma * T up; T <= 64)
  *   seed            the subset of (query q, document i) is Floyd's subset sampling -- for
- *                   j = T-m .. T-1: t = next() mod (j+1); insert t, or j if t is in already --
- *                   on a SplitMix64 stream of its own: one SplitMix64 step from state
+ *                   j = T-m .. T-1: t = floor(next() * (j+1) / 2^64); insert t, or j if t is
+ *                   in already -- on a SplitMix64 stream of its own: one SplitMix64 step from state
  *                   seed + (q+1) * 0x9E3779B97F4A7C15 gives the query's key, the stream of
  *                   document i starts at state key + (i+1) * 0xD1B54A32D192ED03
  *   scores          DEVICE float [n_queries][N]: partial row sums, cells added in ascending

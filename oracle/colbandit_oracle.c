@@ -538,8 +538,8 @@ int oracle_maxsim_cells_i8(const int8_t *Q8, float sq, int T, int d, const int8_
  *
  * The subset of (query q, document i) as a bit mask over [0,T).  Readings (the paper fixes
  * only "uniformly, without replacement"): the draw is Floyd's subset sampling -- for
- * j = T-m .. T-1 take t = next() mod (j+1) and insert t, or j if t is already in -- fed by a
- * SplitMix64 stream of its own per (q, i): one SplitMix64 step from the query's state
+ * j = T-m .. T-1 take t = floor(next() * (j+1) / 2^64), a uniform index in [0, j], and insert
+ * t, or j if t is already in -- fed by a SplitMix64 stream of its own per (q, i): one SplitMix64 step from the query's state
  * seed + (q+1)*0x9E3779B97F4A7C15 gives a query key, and the stream of document i starts at
  * state key + (i+1)*0xD1B54A32D192ED03.  PARITY UNPINNED with respect to the authors'
  * generator, as for the reveal permutation.
@@ -553,7 +553,8 @@ uint64_t oracle_uniform_subset(uint64_t seed, int64_t q, int64_t i, int T, int m
     uint64_t st = key + ((uint64_t)i + 1ULL) * 0xD1B54A32D192ED03ULL;
     uint64_t mask = 0;
     for (int j = T - m; j < T; ++j) {
-        int t = (int)(oracle_splitmix64_next(&st) % (uint64_t)(j + 1));
+        unsigned __int128 wide = (unsigned __int128)oracle_splitmix64_next(&st) * (uint64_t)(j + 1);
+        int t = (int)(uint64_t)(wide >> 64);
         if ((mask >> t) & 1ULL)
             mask |= 1ULL << j;
         else

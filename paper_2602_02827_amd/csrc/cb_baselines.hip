@@ -24,20 +24,13 @@ __device__ __forceinline__ uint64_t mix_next(uint64_t& s) {
     return z ^ (z >> 31);
 }
 
-// z mod n for 1 <= n <= 64 without a 64-bit division: z = hi * 2^32 + lo.
-__device__ __forceinline__ uint32_t mod_small(uint64_t z, uint32_t n) {
-    const uint32_t hi = (uint32_t)(z >> 32), lo = (uint32_t)z;
-    const uint32_t two32 = (uint32_t)(0x100000000ull % n);
-    return ((hi % n) * two32 + lo % n) % n;
-}
-
 // Subset of m of the T query tokens for (query key, document i): Floyd's sampling, driven by a
 // SplitMix64 stream that starts at key + (i+1) * 0xD1B54A32D192ED03.
 __device__ __forceinline__ uint64_t uniform_subset(uint64_t key, int64_t i, int T, int m) {
     uint64_t st = key + ((uint64_t)i + 1ull) * 0xD1B54A32D192ED03ull;
     uint64_t mask = 0;
     for (int j = T - m; j < T; ++j) {
-        const uint32_t t = mod_small(mix_next(st), (uint32_t)(j + 1));
+        const uint32_t t = (uint32_t)__umul64hi(mix_next(st), (uint64_t)(j + 1));   // uniform in [0, j]
         mask |= ((mask >> t) & 1ull) ? (1ull << j) : (1ull << t);
     }
     return mask;
@@ -59,9 +52,18 @@ __global__ __launch_bounds__(256) void k_uniform_score(const float* cells, int64
         const uint64_t R = uniform_subset(key, i, T, m);
         const float* row = cells + ((size_t)q * N + i) * T;
         float s = 0.f;
-        for (int t = 0; t < T; ++t) {
-            const float v = row[t];
-            if ((R >> t) & 1ull) s = s + v;
+        if ((T & 3) == 0) {                  // rows are 16-byte aligned
+            for (int t = 0; t < T; t += 4) {
+                const f32x4_t v = *(const f32x4_t*)(row + t);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if ((R >> (t + e)) & 1ull) s = s + v[e];
+            }
+        } else {
+            for (int t = 0; t < T; ++t) {
+                const float v = row[t];
+                if ((R >> t) & 1ull) s = s + v;
+            }
         }
         scores[(size_t)q * N + i] = s;
         if (masks) masks[(size_t)q * N + i] = R;

@@ -4,11 +4,15 @@
     python -m paper_2602_02827_amd.sweep --config 2 --K 100 500 1000 --M 0 5 10
     python -m paper_2602_02827_amd.sweep --config 2 --nq 1            # single-query latency
     python -m paper_2602_02827_amd.sweep --config 2 --nq 1 --int8     # ... with int8 elimination rounds
+    python -m paper_2602_02827_amd.sweep --config 2 --alpha 0.05 0.1 0.2 0.5 1.0 \
+        --gamma 0.05 0.1 0.2 0.3 0.5 0.7 0.9 1.0 --tau 0.4 0.5 0.6 0.7 0.8 0.9  # quality-coverage frontier
 
 Prints one JSON line per (K, alpha_ef, M): batch latency of colbandit_full_maxsim and of
 colbandit_topk (events around `--reps` back-to-back asynchronous calls), coverage
 (unique revealed cells / (N*T), Sec. 3.1 Eq. (6)), Overlap@K against the exhaustive top-K, mean
-rounds and survivors entering the rescore.  The grid of alpha_ef x K follows the knob sweeps of
+rounds and survivors entering the rescore.  `--gamma` / `--tau` add one line per setting of the
+paper's two non-adaptive baselines, Doc-Uniform and Ball-carving (appendix "Compared Methods"),
+with the same Overlap@K and their coverage (ceil(gamma T)/T, mean k/T).  The grid of alpha_ef x K follows the knob sweeps of
 the paper's evaluation (Sec. 5, implementation appendix "Default parameter setting").
 """
 from __future__ import annotations
@@ -28,6 +32,10 @@ def main(argv=None):
     ap.add_argument("--M", type=int, nargs="+", default=[5])
     ap.add_argument("--B", type=int, default=4)
     ap.add_argument("--reps", type=int, default=3)
+    ap.add_argument("--gamma", type=float, nargs="*", default=[],
+                    help="Doc-Uniform budgets (fraction of the T cells revealed per document)")
+    ap.add_argument("--tau", type=float, nargs="*", default=[],
+                    help="Ball-carving cosine thresholds")
     ap.add_argument("--int8", action="store_true",
                     help="run the elimination rounds on int8 codes of the corpus (coded once, untimed)")
     args = ap.parse_args(argv)
@@ -63,6 +71,40 @@ def main(argv=None):
         ms_full = timed(lambda: B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K, workspace=ws,
                                                         want_scores=False, out=full))
         ids_full = full["topk_ids"].cpu().numpy()
+        overlap_of = lambda ids: float(np.mean([len(set(ids_full[q]) & set(ids[q])) / K for q in range(nq)]))
+        head = {"workload": w.name, "n_queries": nq, "N": N, "T": T, "d": d, "K": K,
+                "full_ms": round(ms_full, 3)}
+        if args.gamma:
+            wsu = torch.empty(int(B.lib().colbandit_doc_uniform_workspace_bytes(nq, T, d, N, total)),
+                              dtype=torch.uint8, device="cuda")
+            for gamma in args.gamma:
+                m = B.cells_per_doc(gamma, T)
+                run = lambda: B.colbandit_doc_uniform(w.Q, w.docs, w.offsets, K, m, seed=w.seed,
+                                                      want_scores=False, workspace=wsu)
+                ms = timed(run)
+                ids = run()["topk_ids"].cpu().numpy()
+                print(json.dumps({**head, "method": "doc_uniform", "gamma": gamma, "cells_per_doc": m,
+                                  "ms": round(ms, 3), "speedup": round(ms_full / ms, 2),
+                                  "coverage": round(m / T, 4), "overlap_at_k": round(overlap_of(ids), 4)}),
+                      flush=True)
+            del wsu
+        if args.tau:
+            wsb = torch.empty(int(B.lib().colbandit_ball_carving_workspace_bytes(nq, T, d, B._dt(w.Q), N, total)),
+                              dtype=torch.uint8, device="cuda")
+            for tau in args.tau:
+                run = lambda: B.colbandit_ball_carving(w.Q, w.docs, w.offsets, K, tau,
+                                                       want_scores=False, workspace=wsb)
+                ms = timed(run)
+                r = run()
+                ids = r["topk_ids"].cpu().numpy()
+                kq = r["n_clusters"].cpu().numpy()
+                print(json.dumps({**head, "method": "ball_carving", "tau": tau, "ms": round(ms, 3),
+                                  "speedup": round(ms_full / ms, 2),
+                                  "coverage": round(float(kq.mean()) / T, 4),
+                                  "mean_clusters": round(float(kq.mean()), 2),
+                                  "columns_scored": int((4 * ((kq + 3) // 4)).sum()),
+                                  "overlap_at_k": round(overlap_of(ids), 4)}), flush=True)
+            del wsb
         for alpha in args.alpha:
             for M in args.M:
                 run = lambda stats=False: B.colbandit_topk(w.Q, w.docs, w.offsets, K, alpha, w.delta, M,
@@ -75,7 +117,8 @@ def main(argv=None):
                 overlap = float(np.mean([len(set(ids_full[q]) & set(ids[q])) / K for q in range(nq)]))
                 cov = sum(s["cells_unique"] for s in st) / (float(nq) * N * T)
                 print(json.dumps({
-                    "workload": w.name, "n_queries": nq, "N": N, "T": T, "d": d, "K": K, "alpha_ef": alpha,
+                    "workload": w.name, "n_queries": nq, "N": N, "T": T, "d": d, "K": K,
+                    "method": "colbandit", "alpha_ef": alpha,
                     "M": M, "B": args.B, "reveals": "int8" if args.int8 else w.dtype, "full_ms": round(ms_full, 3), "colbandit_ms": round(ms_cb, 3),
                     "speedup": round(ms_full / ms_cb, 2), "coverage": round(cov, 4),
                     "overlap_at_k": round(overlap, 4),
