@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--K", type=int, default=5)
     ap.add_argument("--alpha", type=float, default=0.2)
     ap.add_argument("--no-int8", action="store_true", help="skip the int8 coarse-pass leg")
+    ap.add_argument("--no-baselines", action="store_true",
+                    help="skip the Doc-Uniform / Ball-carving operating points")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-docs", type=int, default=60000)
     args = ap.parse_args()
@@ -190,6 +192,46 @@ def main():
                 "corpus_codes_gb": round(total * d / 1e9, 2)}
         del d8
 
+    # the paper's two non-adaptive baselines at one operating point each (appendix "Compared
+    # Methods"): Doc-Uniform at Col-Bandit's own coverage, Ball-carving at tau = 0.8; reported
+    # beside the step, not part of `value`
+    baselines = None
+    if not args.no_baselines and T <= 64:
+        def timed_ms(fn):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                r = fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.steps, r
+
+        overlap_of = lambda ids: round(float(np.mean([len(set(ids_full[q]) & set(ids[q])) / K
+                                                      for q in range(nq)])), 4)
+        m = B.cells_per_doc(coverage, T)
+        wsu = torch.empty(int(B.lib().colbandit_doc_uniform_workspace_bytes(nq, T, d, N, total)),
+                          dtype=torch.uint8, device=dev)
+        ms_u, ru = timed_ms(lambda: B.colbandit_doc_uniform(w.Q, w.docs, w.offsets, K, m, seed=w.seed,
+                                                            want_scores=False, workspace=wsu))
+        ids_u = ru["topk_ids"].cpu().numpy()
+        del wsu, ru
+        tau = 0.8
+        wsb = torch.empty(int(B.lib().colbandit_ball_carving_workspace_bytes(nq, T, d, B._dt(w.Q), N, total)),
+                          dtype=torch.uint8, device=dev)
+        ms_b, rb = timed_ms(lambda: B.colbandit_ball_carving(w.Q, w.docs, w.offsets, K, tau,
+                                                             want_scores=False, workspace=wsb))
+        kq = rb["n_clusters"].cpu().numpy()
+        baselines = {
+            "doc_uniform": {"cells_per_doc": m, "coverage": round(m / T, 4), "ms": round(ms_u, 3),
+                            "overlap_at_k": overlap_of(ids_u), "speedup_vs_full": round(ms_full / ms_u, 2)},
+            "ball_carving": {"tau": tau, "mean_clusters": round(float(kq.mean()), 2),
+                             "coverage": round(float(kq.mean()) / T, 4), "ms": round(ms_b, 3),
+                             "overlap_at_k": overlap_of(rb["topk_ids"].cpu().numpy()),
+                             "speedup_vs_full": round(ms_full / ms_b, 2)}}
+        del wsb, rb
+
     flops_full = 2.0 * nq * T * d * total
     tflops = flops_full / (ms_full * 1e-3) / 1e12
     ms_dense = float(np.mean([m[0] for m in ms_kernel]))
@@ -253,6 +295,7 @@ def main():
                                      "ms_rescore_topk")},
                       "survivor_scores_bit_identical_to_full": same_bits},
         "colbandit_int8": int8,
+        "baselines": baselines,
         "roofline": roofline,
         "roofline_gather": gather,
         "paper_context": "paper (CPU, real embeddings): up to ~8x fewer MaxSim FLOPs, up to ~13x "
