@@ -46,5 +46,20 @@ def build_library(force: bool = False, verbose: bool = False) -> str:
     return LIB
 
 
+ABI_CHECK_SRC = os.path.join(HERE, "..", "tests", "native", "abi_check.cpp")
+ABI_CHECK = os.path.join(HERE, "..", "tests", "native", "abi_check.bin")
+
+
+def build_abi_check() -> str:
+    """Compiles tests/native/abi_check.cpp, a plain C++ host program that drives the C-ABI
+    without Python, against the built library (found at run time through its rpath)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-x", "hip", ABI_CHECK_SRC,
+           "-x", "none", "-L" + HERE, "-lcolbandit",
+           "-Wl,-rpath,$ORIGIN/../../paper_2602_02827_amd", "-o", ABI_CHECK]
+    subprocess.run(cmd, check=True)
+    return ABI_CHECK
+
+
 if __name__ == "__main__":
     print(build_library(force=True, verbose=True))

@@ -854,3 +854,17 @@ def test_full_size_baselines_on_sampled_documents(B, oracle_mod, big):
         np.testing.assert_allclose(got, So, rtol=TOL["bf16"], atol=1e-3)
         sc = rb["scores"][q].cpu().numpy()
         np.testing.assert_array_equal(rb["topk_ids"][q].cpu().numpy(), np.lexsort((np.arange(w.N), -sc))[:K])
+
+
+# ------------------------------------------------------------------ the C-ABI without Python
+def test_c_abi_from_a_plain_host_program(B):
+    """tests/native/abi_check.cpp drives the library with hipMalloc'ed buffers and its own
+    stream (no torch anywhere in the process) and checks scores against the definition."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "native", "abi_check.bin")
+    if not os.path.exists(exe):
+        pytest.skip("tests/native/abi_check.bin is not built (__graft_entry__.build() builds it)")
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "abi_check ok" in r.stdout
