@@ -555,6 +555,17 @@ def test_doc_uniform_subsets_have_the_stated_size_and_are_uniform(oracle_mod):
     assert [oracle_mod.uniform_subset(7, 3, i, T, m) for i in range(50)] == masks[:50]
 
 
+def test_doc_uniform_generator_is_frozen(oracle_mod):
+    """The subset generator is this build's own definition; tests/golden/uniform_subsets.txt
+    (written by make_uniform_subsets.py from the oracle) freezes it, so that a change of the
+    stream or of the index map cannot pass unnoticed on both sides at once."""
+    rows = _golden_rows("uniform_subsets.txt")
+    assert len(rows) >= 10
+    for seed, q, i, T, m, mask in rows:
+        got = oracle_mod.uniform_subset(int(seed), int(q), int(i), int(T), int(m))
+        assert got == int(mask, 16) and _popcount(got) == int(m)
+
+
 def test_doc_uniform_scores_are_partial_row_sums_and_full_budget_is_exhaustive(oracle_mod):
     """Doc-Uniform paragraph: the prediction ranks documents by the sum of their revealed
     cells; at gamma = 1 every cell is revealed and the ranking is the exhaustive one (Eq. (3))."""
