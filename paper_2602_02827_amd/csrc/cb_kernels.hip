@@ -878,8 +878,55 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
         sel_count = filter(std::integral_constant<int, SEL_ITEMS_WIDE>{}, in, count, out, tau_lo, false);
         sel_in = out;
     }
-    auto key_sel = [&](int idx) -> uint32_t { return key_of(sel_in, idx); };
-    const uint32_t tkey = block_kth_largest(sel_count, A.K, key_sel, hist, pick);
+    uint32_t tkey;
+    if (sel_count > SEL_PREFILTER_MIN) {
+        // Still a long list (a conservative radius prunes little): the exact threshold depends
+        // only on the entries whose LCB reaches a sampled lower threshold (the K-th largest of
+        // a subset cannot exceed that of the whole list, so these include the K largest).  One
+        // pass collects them, in any order, into the list buffer that this round no longer
+        // reads; the three radix passes then run over those few instead of the whole list.
+        auto key_s = [&](int j) -> uint32_t { return key_of(sel_in, sample_pos(j, sel_count)); };
+        const uint32_t lo_key = block_kth_largest_sample(A.K, key_s, hist, pick);
+        int32_t* few = (out_sel ? A.list0 : A.list1) + (size_t)q * A.N;   // sel_in == out here
+        if (threadIdx.x == 0) pick[0] = 0;
+        __syncthreads();
+        const int lane = threadIdx.x & 63;
+        for (int base0 = 0; base0 < sel_count; base0 += SEL_CHUNK) {
+            int e[SEL_ITEMS];
+            bool on[SEL_ITEMS];
+#pragma unroll
+            for (int u = 0; u < SEL_ITEMS; ++u) {
+                const int idx = base0 + u * SEL_THREADS + (int)threadIdx.x;
+                e[u] = idx < sel_count ? sel_in[idx] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < SEL_ITEMS; ++u) {
+                const int idx = base0 + u * SEL_THREADS + (int)threadIdx.x;
+                float lcb, ucb;
+                const float2 st = stat[e[u]];
+                interval(st.x, st.y, n, T, kappa, a, b, lcb, ucb);
+                on[u] = idx < sel_count && float_key(lcb) >= lo_key;
+            }
+#pragma unroll
+            for (int u = 0; u < SEL_ITEMS; ++u) {
+                const unsigned long long m = __ballot(on[u]);
+                if (m != 0ull) {                            // uniform over the wavefront
+                    int at = 0;
+                    if (lane == 0) at = atomicAdd(&pick[0], __popcll(m));
+                    at = __shfl(at, 0);
+                    if (on[u]) few[at + __popcll(m & ((1ull << lane) - 1ull))] = e[u];
+                }
+            }
+        }
+        __syncthreads();
+        const int n_few = pick[0];
+        __syncthreads();
+        auto key_few = [&](int idx) -> uint32_t { return key_of(few, idx); };
+        tkey = block_kth_largest(n_few, A.K, key_few, hist, pick);
+    } else {
+        auto key_sel = [&](int idx) -> uint32_t { return key_of(sel_in, idx); };
+        tkey = block_kth_largest(sel_count, A.K, key_sel, hist, pick);
+    }
     const float tau = key_float(tkey);
     const int base = filter(std::integral_constant<int, SEL_ITEMS>{}, sel_in, sel_count, out, tau, true);
 
