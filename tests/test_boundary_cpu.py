@@ -100,6 +100,7 @@ def test_topk_argument_errors(B):
     assert _call_topk(B, M=-1) == -3
     assert _call_topk(B, opts=B.ColbanditOpts(B=-2)) == -3
     assert _call_topk(B, opts=B.ColbanditOpts(B=17)) == -4
+    assert _call_topk(B, T=66, opts=B.ColbanditOpts(B=1)) == -4      # 66 rounds > the 64-round limit
     assert _call_topk(B, T=128, opts=B.ColbanditOpts(B=1)) == -4       # more than 64 rounds
     assert _call_topk(B, opts=B.ColbanditOpts(a=1.0, b=-1.0)) == -3
     assert _call_topk(B, opts=B.ColbanditOpts(a=0.5, b=0.5)) == -3

@@ -430,6 +430,7 @@ def test_colbandit_small_candidate_sets(B, S, oracle_mod):
     (3, 40, 64, 400, 4, 3, 5, 0.5, True),           # int8 rounds with d=64 and B not dividing T
     (2, 100, 128, 300, 5, 5, 7, 1.0, True),         # int8 rounds, 7 tiles of query tokens
     (4, 32, 128, 6, 5, 5, 4, 0.2, True),            # N <= K + M: no round at all
+    (2, 64, 128, 300, 5, 5, 1, 0.6, False),         # one token per round: the 64-round limit
 ])
 def test_colbandit_corner_shapes(B, S, oracle_mod, nq, T, d, N, K, M, Bsz, alpha, coarse):
     rng = np.random.default_rng(N + T)
