@@ -857,6 +857,59 @@ def test_full_size_baselines_on_sampled_documents(B, oracle_mod, big):
         np.testing.assert_array_equal(rb["topk_ids"][q].cpu().numpy(), np.lexsort((np.arange(w.N), -sc))[:K])
 
 
+@pytest.mark.parametrize("idx,shape", [(1, (50000, 64, 32)), (3, (20000, 64, 24)), (4, (100000, 256, 32))])
+def test_other_configurations_at_full_size(B, S, oracle_mod, idx, shape):
+    """The mid-text, page-like and knob-sweep configurations at their full sizes: exhaustive
+    scores of sampled documents against the oracle, then properties that hold at any size -
+    the top-K is the ordered head of the score rows, Col-Bandit (bf16 reveals and int8 reveals)
+    returns distinct valid documents with the exhaustive path's score bits, the cell accounting
+    adds up, and the planted documents of the mid-text corpus are found."""
+    print(f"generating configuration {idx} at full size ...", flush=True)
+    w = S.config(idx, device="cuda")
+    assert (w.N, w.nq, w.T) == shape and w.dtype == "bf16"
+    K, T = w.K, w.T
+    ws = B.new_workspace(w.nq, T, w.d, w.N, w.total_tokens, "cuda")
+    full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K, workspace=ws)
+    res = B.colbandit_topk(w.Q, w.docs, w.offsets, K, w.alpha_ef, w.delta, w.M, w.seed, workspace=ws)
+    d8, ds = B.colbandit_quantize_i8(w.docs)
+    res8 = B.colbandit_topk(w.Q, w.docs, w.offsets, K, w.alpha_ef, w.delta, w.M, w.seed, workspace=ws,
+                            docs_i8=d8, docs_scale=ds)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(idx)
+    qs = [0, w.nq // 2, w.nq - 1]
+    Qh = w.host_queries(qs)
+    ids_full = full["topk_ids"].cpu().numpy()
+    for j, q in enumerate(qs):
+        docs = np.unique(np.concatenate([rng.integers(0, w.N, 12), [0, w.N - 1], ids_full[q]]))
+        E, off = w.host_docs(docs.tolist())
+        want = oracle_mod.maxsim_cells(Qh[j], E, off).sum(axis=1)
+        got = full["scores"][q][torch.as_tensor(docs, device="cuda")].cpu().numpy()
+        np.testing.assert_allclose(got, want, rtol=TOL["bf16"], atol=0)
+        sc = full["scores"][q].cpu().numpy()
+        order = np.lexsort((np.arange(w.N), -sc))[:K]
+        np.testing.assert_array_equal(ids_full[q], order)
+        np.testing.assert_array_equal(full["topk_scores"][q].cpu().numpy(), sc[order])
+    for r in (res, res8):
+        ids = r["topk_ids"]
+        assert bool((ids >= 0).all()) and bool((ids < w.N).all())
+        assert all(len(set(row)) == K for row in ids.tolist())
+        assert torch.equal(r["topk_scores"], torch.gather(full["scores"], 1, ids))
+        for st in r["stats"]:
+            surv = st["survivors"]
+            assert surv[0] == w.N and all(surv[k + 1] <= surv[k] for k in range(st["rounds"]))
+            assert surv[st["rounds"]] >= K
+            cells = sum((min((k + 1) * w.B, T) - k * w.B) * surv[k] for k in range(st["rounds"]))
+            assert st["cells_elim"] == cells and st["cells_rescore"] == T * surv[st["rounds"]]
+            assert st["cells_unique"] <= w.N * T
+    if idx == 1:      # the five strongest planted documents of each query win the exhaustive top-5
+        for q in range(w.nq):
+            assert set(ids_full[q].tolist()) <= set(w.planted[q])
+    overlap = np.mean([len(set(ids_full[q]) & set(res["topk_ids"][q].tolist())) / K for q in range(w.nq)])
+    print(f"configuration {idx}: Overlap@{K} {overlap:.3f}, "
+          f"coverage {sum(s['cells_unique'] for s in res['stats']) / (w.nq * w.N * T):.3f}", flush=True)
+    assert overlap >= 0.5
+
+
 # ------------------------------------------------------------------ the C-ABI without Python
 def test_c_abi_from_a_plain_host_program(B):
     """tests/native/abi_check.cpp drives the library with hipMalloc'ed buffers and its own
