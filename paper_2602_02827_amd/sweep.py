@@ -27,6 +27,7 @@ def main(argv=None):
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--nq", type=int, default=None)
+    ap.add_argument("--d", type=int, default=128, help="embedding width (128, or 64)")
     ap.add_argument("--alpha", type=float, nargs="+", default=[0.2])
     ap.add_argument("--K", type=int, nargs="+", default=[5])
     ap.add_argument("--M", type=int, nargs="+", default=[5])
@@ -46,7 +47,7 @@ def main(argv=None):
 
     assert torch.cuda.is_available(), "sweep needs a GPU"
     B.lib()
-    w = synth.config(args.config, device="cuda", scale=args.scale, nq=args.nq)
+    w = synth.config(args.config, device="cuda", scale=args.scale, nq=args.nq, d=args.d)
     nq, T, d, N, total = w.nq, w.T, w.d, w.N, w.total_tokens
     ws = B.new_workspace(nq, T, d, N, total, "cuda")
 

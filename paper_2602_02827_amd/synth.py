@@ -241,23 +241,25 @@ def pages(name, N, L_page, nq, T, d, dtype, n_centroids, seed, device="cpu",
 # The five measured configurations.  `scale` shrinks N (and nothing else) so that the
 # same recipe can serve quick tests.
 def config(idx: int, device="cpu", scale: float = 1.0, nq: int | None = None,
-           seed: int | None = None) -> Workload:
+           seed: int | None = None, d: int = 128) -> Workload:
+    """The five synthetic configurations; `d` other than 128 gives the same recipe at another
+    embedding width (64: the shape of the paper's Matryoshka-projection experiment)."""
     def n(x):
         return max(64, int(round(x * scale)))
 
     if idx == 0:   # tiny text rerank, fp32
-        return text_iid("C1-tiny-text-f32", n(1000), 32, 64, nq or 1, 32, 128, "f32", 5, (0.3,),
+        return text_iid("C1-tiny-text-f32", n(1000), 32, 64, nq or 1, 32, d, "f32", 5, (0.3,),
                         0 if seed is None else seed, device)
     if idx == 1:   # mid text rerank, bf16
-        return text_iid("C2-mid-text-bf16", n(50_000), 32, 180, nq or 64, 32, 128, "bf16", 20,
+        return text_iid("C2-mid-text-bf16", n(50_000), 32, 180, nq or 64, 32, d, "bf16", 20,
                         (0.2, 0.4, 0.6), 1 if seed is None else seed, device)
     if idx == 2:   # large text corpus, bf16
-        return text_topics("C3-large-text-bf16", n(500_000), 32, 180, nq or 128, 32, 128, "bf16",
+        return text_topics("C3-large-text-bf16", n(500_000), 32, 180, nq or 128, 32, d, "bf16",
                            1024, 2 if seed is None else seed, device)
     if idx == 3:   # multimodal page-like corpus, bf16
-        return pages("C4-pages-bf16", n(20_000), 1030, nq or 64, 24, 128, "bf16", 256,
+        return pages("C4-pages-bf16", n(20_000), 1030, nq or 64, 24, d, "bf16", 256,
                      3 if seed is None else seed, device)
     if idx == 4:   # knob sweep corpus, bf16
-        return text_topics("C5-sweep-bf16", n(100_000), 32, 180, nq or 256, 32, 128, "bf16", 512,
+        return text_topics("C5-sweep-bf16", n(100_000), 32, 180, nq or 256, 32, d, "bf16", 512,
                            4 if seed is None else seed, device)
     raise ValueError("config index must be 0..4")
