@@ -120,6 +120,11 @@ typedef struct {
     float ms_rescore_topk;                            /* rescore and final top-K
                                                          (cf. the paper's stage split in
                                                          its overhead-breakdown table)  */
+    uint32_t pad0;
+    uint64_t corpus_pass_rounds;                      /* bit r-1 set: the batch revealed
+                                                         round r (r >= 2) by one pass over
+                                                         the corpus instead of per-pair
+                                                         gathers (same for all queries)  */
 } colbandit_stats;
 
 /* sizeof(colbandit_opts) / sizeof(colbandit_stats) as this library was compiled: lets a

@@ -613,6 +613,8 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
     const bool dense = dense_supported(P, co) && !force_gather;
     int n_chunks = 0;
     if (e == hipSuccess && loop && dense) e = launch_dense_prepare(P, W, kChunkTokens, &n_chunks, st);
+    unsigned long long round_thr[COLBANDIT_MAX_ROUNDS + 2];
+    for (int r = 0; r <= R + 1; ++r) round_thr[r] = ~0ull;
     for (int r = 1; e == hipSuccess && loop && r <= R; ++r) {
         RevealRound rr{};
         rr.r = r;
@@ -630,6 +632,7 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
         } else {
             if (r >= 2 && dense && later_rounds != 2)
                 rr.dense_thr = later_rounds == 1 ? 0ull : dense_pairs_threshold(P, G, co != nullptr);
+            round_thr[r] = rr.dense_thr;
             e = launch_dense_reveal_later(P, W, kChunkTokens, n_chunks, rr, G, co, st);
             if (e == hipSuccess) e = launch_gather_reveal(P, W, rr, co, st);
             if (e == hipSuccess && r >= 2) e = launch_gather_cells(P, W, rr, co, st);
@@ -654,7 +657,15 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
     int32_t* hist = (int32_t*)malloc(sizeof(int32_t) * nh);
     if (!hist) { pt.destroy(); return COLBANDIT_ERR_HIP; }
     hipError_t ce = hipMemcpyAsync(hist, W.cnt_hist, sizeof(int32_t) * nh, hipMemcpyDeviceToHost, st);
+    unsigned long long pairs_h[COLBANDIT_MAX_ROUNDS + 2];
+    if (ce == hipSuccess)
+        ce = hipMemcpyAsync(pairs_h, W.pairs, sizeof(unsigned long long) * (size_t)(R + 2),
+                            hipMemcpyDeviceToHost, st);
     if (ce == hipSuccess) ce = hipStreamSynchronize(st);
+    // the rounds whose device-side test took the corpus pass (the same test as the kernels')
+    uint64_t corpus_rounds = 0;
+    for (int r = 2; ce == hipSuccess && loop && r <= R; ++r)
+        if (round_thr[r] != ~0ull && pairs_h[r] > round_thr[r]) corpus_rounds |= 1ull << (r - 1);
     float ms = 0.f, phase_ms[PH_COUNT] = {0.f, 0.f, 0.f, 0.f};
     if (ce == hipSuccess) pt.collect(phase_ms, ms);
     pt.destroy();
@@ -681,6 +692,7 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
         s.ms_later_reveals = phase_ms[PH_LATER_REVEAL];
         s.ms_select_prune = phase_ms[PH_SELECT];
         s.ms_rescore_topk = phase_ms[PH_RESCORE];
+        s.corpus_pass_rounds = corpus_rounds;
     }
     free(hist);
     return COLBANDIT_OK;

@@ -284,7 +284,8 @@ def _same_run(r1, r2):
     for f in ("count", "tau", "lcb", "ucb", "alive"):
         np.testing.assert_array_equal(getattr(r1["trace"], f), getattr(r2["trace"], f))
     assert torch.equal(r1["topk_ids"], r2["topk_ids"]) and torch.equal(r1["topk_scores"], r2["topk_scores"])
-    counts = lambda st: {k: v for k, v in st.items() if not k.startswith("ms_")}
+    # which path computed a round's cells may differ between the runs; nothing else may
+    counts = lambda st: {k: v for k, v in st.items() if not k.startswith("ms_") and k != "corpus_pass_rounds"}
     assert [counts(a) for a in r1["stats"]] == [counts(b) for b in r2["stats"]]
 
 
@@ -314,6 +315,12 @@ def test_later_rounds_by_corpus_pass_or_by_gather_are_identical(B, S, oracle_mod
     assert max(s["rounds"] for s in runs[0]["stats"]) >= 3
     _same_run(runs[0], runs[1])
     _same_run(runs[0], runs[2])
+    # the statistics name the rounds that streamed the corpus: none when gathers are forced,
+    # every round >= 2 that still had an ids-mode query when the pass is forced
+    assert all(s["corpus_pass_rounds"] == [] for s in runs[0]["stats"])
+    forced = runs[1]["stats"][0]["corpus_pass_rounds"]
+    assert forced and forced[0] == 2 and forced == list(range(2, 2 + len(forced)))
+    assert set(runs[2]["stats"][0]["corpus_pass_rounds"]) <= set(forced)
     # the streaming pass also under the cache-free mode, and against the oracle
     r3 = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, alpha, 0.01, 5, 4, B=Bsz, trace=True,
                           later_rounds=1, no_cell_cache=True)
@@ -335,8 +342,9 @@ def test_device_side_choice_takes_the_corpus_pass_for_large_active_sets(B, S):
     torch.cuda.synchronize()
     assert torch.equal(res[0]["topk_ids"], res[2]["topk_ids"])
     assert torch.equal(res[0]["topk_scores"], res[2]["topk_scores"])
-    c = lambda st: {k: v for k, v in st.items() if not k.startswith("ms_")}
+    c = lambda st: {k: v for k, v in st.items() if not k.startswith("ms_") and k != "corpus_pass_rounds"}
     assert [c(a) for a in res[0]["stats"]] == [c(b) for b in res[2]["stats"]]
+    assert 2 in res[0]["stats"][0]["corpus_pass_rounds"] and res[2]["stats"][0]["corpus_pass_rounds"] == []
     print("later reveals: auto %.3f ms, gather %.3f ms" %
           (res[0]["stats"][0]["ms_later_reveals"], res[2]["stats"][0]["ms_later_reveals"]))
 
