@@ -210,7 +210,7 @@ def main():
 
         overlap_of = lambda ids: round(float(np.mean([len(set(ids_full[q]) & set(ids[q])) / K
                                                       for q in range(nq)])), 4)
-        m = B.cells_per_doc(coverage, T)
+        m = B.colbandit_cells_per_doc(coverage, T)
         wsu = torch.empty(int(B.lib().colbandit_doc_uniform_workspace_bytes(nq, T, d, N, total)),
                           dtype=torch.uint8, device=dev)
         ms_u, ru = timed_ms(lambda: B.colbandit_doc_uniform(w.Q, w.docs, w.offsets, K, m, seed=w.seed,

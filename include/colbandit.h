@@ -245,7 +245,7 @@ int colbandit_topk(const void *Q, int n_queries, int T, int d, colbandit_dtype d
  * Doc-Uniform paragraph and its algorithm box): every (query, document) pair reveals its own
  * uniformly drawn subset of `cells_per_doc` = ceil(gamma * T) query tokens, without
  * replacement, and documents are ranked by the sum of the revealed cells.
- *   cells_per_doc   1 .. T (the caller rounds gamma * T up; T <= 64)
+ *   cells_per_doc   1 .. T (colbandit_cells_per_doc turns a coverage gamma into it; T <= 64)
  *   seed            the subset of (query q, document i) is Floyd's subset sampling -- for
  *                   j = T-m .. T-1: t = floor(next() * (j+1) / 2^64); insert t, or j if t is
  *                   in already -- on a SplitMix64 stream of its own: one SplitMix64 step from state
@@ -263,6 +263,15 @@ int colbandit_topk(const void *Q, int n_queries, int T, int d, colbandit_dtype d
  */
 size_t colbandit_doc_uniform_workspace_bytes(int n_queries, int T, int d, int64_t N,
                                              int64_t total_tokens);
+/*
+ * Cells per document of Doc-Uniform at coverage gamma (first line of its algorithm box in the
+ * appendix "Compared Methods": ceil(gamma * T) cells per row).  gamma is a decimal knob (the
+ * paper sweeps 0.05, 0.10, ..., 1.00) whose nearest double can lie a hair above the decimal,
+ * so a product within 1e-9 of an integer counts as that integer: 0.1 * 30 gives 3, not 4.
+ * Returns ceil(gamma * T - 1e-9) clamped to [1, T], or COLBANDIT_ERR_KNOB unless
+ * 0 < gamma <= 1, COLBANDIT_ERR_SHAPE unless T >= 1.  Pure host code.
+ */
+int colbandit_cells_per_doc(double gamma, int T);
 int colbandit_doc_uniform(const void *Q, int n_queries, int T, int d, colbandit_dtype dt,
                           const void *doc_tokens, const int64_t *doc_offsets, int64_t N,
                           int64_t total_tokens, int K, int cells_per_doc, uint64_t seed,

@@ -240,6 +240,43 @@ def colbandit_coarse(H_coarse, H_exact, K, M, B, alpha, delta, pi, a=-1.0, b=1.0
                            None if alive is None else alive[:rc].astype(bool))
 
 
+def colbandit_resume(H, K, M, B, alpha, delta, pi, active_ids, r0, a=-1.0, b=1.0, H_exact=None):
+    """Algorithm 1 entered at round r0 (1-based) with the active set `active_ids` (ascending
+    document indices) whose first (r0-1)*B cells of the shared order count as revealed.  The
+    result's per-round arrays are indexed by absolute round: entries below r0-1 are the
+    initial fill (NaN / -1 / False); `rounds` is the index of the last executed round;
+    cells_elim counts the resumed rounds only.  H_exact: exact cells for the rescore when H
+    holds coarse ones."""
+    H = np.ascontiguousarray(H, dtype=np.float64)
+    He = None if H_exact is None else np.ascontiguousarray(H_exact, dtype=np.float64)
+    N, T = H.shape
+    pi = np.ascontiguousarray(pi, dtype=np.int32)
+    A0 = _i64(active_ids)
+    Rmax = (T + B - 1) // B
+    out_ids = np.full(K, -1, dtype=np.int64)
+    out_s = np.full(K, np.nan, dtype=np.float64)
+    final_ids = np.empty(N, dtype=np.int64)
+    n_final = ctypes.c_int64(0)
+    counts = np.full(Rmax + 1, -1, dtype=np.int64)
+    tau = np.full(Rmax, np.nan, dtype=np.float64)
+    cells = np.zeros(3, dtype=np.int64)
+    lcb = np.empty((Rmax, N), dtype=np.float64)
+    ucb = np.empty((Rmax, N), dtype=np.float64)
+    alive = np.empty((Rmax, N), dtype=np.uint8)
+    rc = _check(_L().oracle_colbandit_resume(
+        _p(H, ctypes.c_double), _p(He, ctypes.c_double), ctypes.c_int64(N), T, K, M, B,
+        ctypes.c_double(alpha), ctypes.c_double(delta), ctypes.c_double(a), ctypes.c_double(b),
+        _p(pi, ctypes.c_int32), _p(A0, ctypes.c_int64), ctypes.c_int64(A0.shape[0]), int(r0),
+        _p(out_ids, ctypes.c_int64), _p(out_s, ctypes.c_double),
+        _p(final_ids, ctypes.c_int64), ctypes.byref(n_final), _p(counts, ctypes.c_int64),
+        _p(tau, ctypes.c_double), _p(lcb, ctypes.c_double), _p(ucb, ctypes.c_double),
+        _p(alive, ctypes.c_uint8), _p(cells, ctypes.c_int64)), "colbandit_resume")
+    return ColBanditResult(out_ids, out_s, final_ids[: n_final.value].copy(), rc,
+                           counts[: rc + 1].copy(), tau[:rc].copy(),
+                           int(cells[0]), int(cells[1]), int(cells[2]),
+                           lcb[:rc], ucb[:rc], alive[:rc].astype(bool))
+
+
 def abs_percentile(x, permille=999) -> float:
     """Nearest-rank percentile (permille/1000) of |x| over all entries of x."""
     x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
@@ -273,6 +310,12 @@ def maxsim_cells_i8(Q8, sq, D8, sd, offsets):
                                        _p(H, ctypes.c_double), _p(Hint, ctypes.c_int32)),
            "maxsim_cells_i8")
     return H, Hint
+
+
+def cells_per_doc(gamma, T) -> int:
+    """ceil(gamma * T) of Doc-Uniform's algorithm box (decimal gamma, see the C source)."""
+    _L().oracle_cells_per_doc.argtypes = [ctypes.c_double, ctypes.c_int]
+    return _check(_L().oracle_cells_per_doc(float(gamma), int(T)), "cells_per_doc")
 
 
 def uniform_subset(seed, q, i, T, m) -> int:

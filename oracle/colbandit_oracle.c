@@ -295,10 +295,22 @@ static int cmp_desc(const void *pa, const void *pb)
  *   cells [3]                     cells_elim, cells_rescore, cells_unique
  * Rmax = ceil(T/B).  Returns the number of executed rounds (>= 0) or a
  * negative error.
+ *
+ * Resuming (A0 != NULL): the loop is entered at round r0 >= 1 with the active
+ * set A0[0..nA0) (document indices, strictly ascending) instead of round 1
+ * with all N documents.  Every member of A0 then already has the
+ * (r0-1)*B cells pi[0 .. (r0-1)B) revealed, exactly as after r0-1 rounds of
+ * an uninterrupted run (the shared reveal order makes that state a function
+ * of the active set alone).  N inside the radius stays the candidate count
+ * of the call.  counts[r0-1] = nA0; entries of counts, tau and the trace
+ * below round r0 are left as initialised; cells_elim counts the resumed
+ * rounds only.  The return value is still the index of the last executed
+ * round (r0-1 if none ran).
  */
 static int colbandit_core(const cell_source_t *src, int64_t N, int K, int M, int B,
                           double alpha, double delta, double a, double b,
                           const int32_t *pi,
+                          const int64_t *A0, int64_t nA0, int r0,
                           int64_t *out_ids, double *out_scores,
                           int64_t *final_ids, int64_t *n_final,
                           int64_t *counts, double *tau,
@@ -310,6 +322,13 @@ static int colbandit_core(const cell_source_t *src, int64_t N, int K, int M, int
         !(delta > 0.0) || !(delta < 1.0) || !(a < b))
         return ORACLE_ERR_ARG;
     const int Rmax = (T + B - 1) / B;
+    if (A0) {
+        if (r0 < 1 || r0 > Rmax + 1 || nA0 < 1 || nA0 > N)
+            return ORACLE_ERR_ARG;
+        for (int64_t x = 0; x < nA0; ++x)
+            if (A0[x] < 0 || A0[x] >= N || (x > 0 && A0[x] <= A0[x - 1]))
+                return ORACLE_ERR_ARG;
+    }
 
     int64_t *A = (int64_t *)malloc(sizeof(int64_t) * (size_t)N);      /* active set   */
     double *vals = (double *)malloc(sizeof(double) * (size_t)N * T);  /* revealed     */
@@ -337,7 +356,20 @@ static int colbandit_core(const cell_source_t *src, int64_t N, int K, int M, int
     int n = 0;              /* revealed cells per active document (same for all) */
     int r = 1;
     int64_t cells_elim = 0;
-    if (counts) counts[0] = N;
+    if (A0) {
+        /* the state after r0-1 rounds: active set A0, first (r0-1)B cells of pi revealed */
+        nA = nA0;
+        r = r0;
+        n = (r0 - 1) * B < T ? (r0 - 1) * B : T;
+        for (int64_t x = 0; x < nA; ++x) {
+            A[x] = A0[x];
+            for (int p = 0; p < n; ++p)
+                vals[(size_t)A0[x] * T + p] = reveal(src, A0[x], pi[p]);
+        }
+        if (counts) counts[r0 - 1] = nA0;
+    } else if (counts) {
+        counts[0] = N;
+    }
 
     while (nA > (int64_t)K + M && (r - 1) * B < T) {
         int lo = (r - 1) * B;
@@ -411,8 +443,31 @@ int oracle_colbandit_from_H(const double *H, int64_t N, int T, int K, int M, int
     if (!H || T < 1)
         return ORACLE_ERR_ARG;
     cell_source_t src = {H, NULL, NULL, NULL, T, 0, NULL};
-    return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, out_ids, out_scores,
-                          final_ids, n_final, counts, tau, tr_lcb, tr_ucb, tr_alive, cells);
+    return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, NULL, 0, 1, out_ids,
+                          out_scores, final_ids, n_final, counts, tau, tr_lcb, tr_ucb, tr_alive,
+                          cells);
+}
+
+/*
+ * The same loop entered at round r0 with the active set A0 (see colbandit_core): what
+ * Algorithm 1 does from the state "A_{r0} = A0, (r0-1)B cells of the shared order revealed".
+ * H_exact may be NULL (then the rescore reads H, as in oracle_colbandit_from_H).
+ */
+int oracle_colbandit_resume(const double *H, const double *H_exact, int64_t N, int T, int K,
+                            int M, int B, double alpha, double delta, double a, double b,
+                            const int32_t *pi, const int64_t *A0, int64_t nA0, int r0,
+                            int64_t *out_ids, double *out_scores,
+                            int64_t *final_ids, int64_t *n_final,
+                            int64_t *counts, double *tau,
+                            double *tr_lcb, double *tr_ucb, uint8_t *tr_alive,
+                            int64_t *cells)
+{
+    if (!H || !A0 || T < 1)
+        return ORACLE_ERR_ARG;
+    cell_source_t src = {H, NULL, NULL, NULL, T, 0, H_exact};
+    return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, A0, nA0, r0, out_ids,
+                          out_scores, final_ids, n_final, counts, tau, tr_lcb, tr_ucb, tr_alive,
+                          cells);
 }
 
 /*
@@ -432,8 +487,9 @@ int oracle_colbandit_coarse(const double *H_coarse, const double *H_exact, int64
     if (!H_coarse || !H_exact || T < 1)
         return ORACLE_ERR_ARG;
     cell_source_t src = {H_coarse, NULL, NULL, NULL, T, 0, H_exact};
-    return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, out_ids, out_scores,
-                          final_ids, n_final, counts, tau, tr_lcb, tr_ucb, tr_alive, cells);
+    return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, NULL, 0, 1, out_ids,
+                          out_scores, final_ids, n_final, counts, tau, tr_lcb, tr_ucb, tr_alive,
+                          cells);
 }
 
 /* ------------------------------------------------------------------ */
@@ -544,6 +600,23 @@ int oracle_maxsim_cells_i8(const int8_t *Q8, float sq, int T, int d, const int8_
  * state key + (i+1)*0xD1B54A32D192ED03.  PARITY UNPINNED with respect to the authors'
  * generator, as for the reveal permutation.
  */
+/*
+ * Budget of Doc-Uniform: "ceil(gamma T) cells per row" (first line of its algorithm box).
+ * gamma is a decimal knob; the smallest integer m with m >= gamma*T is searched upwards, and a
+ * product that exceeds an integer by less than 1e-9 (binary representation of the decimal)
+ * counts as that integer.  Clamped to [1, T].  Negative on bad arguments.
+ */
+int oracle_cells_per_doc(double gamma, int T)
+{
+    if (T < 1 || !(gamma > 0.0) || !(gamma <= 1.0))
+        return ORACLE_ERR_ARG;
+    const double want = gamma * (double)T;
+    for (int m = 1; m < T; ++m)
+        if ((double)m + 1e-9 >= want)
+            return m;
+    return T;
+}
+
 uint64_t oracle_uniform_subset(uint64_t seed, int64_t q, int64_t i, int T, int m)
 {
     if (T < 1 || T > 64 || m < 0 || m > T)
@@ -722,8 +795,8 @@ int oracle_colbandit_lazy(const float *Q, int T, int d, const float *E,
         if (off[i + 1] <= off[i])
             return ORACLE_ERR_EMPTY_DOC;
     cell_source_t src = {NULL, Q, E, off, T, d, NULL};
-    return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, out_ids, out_scores,
-                          final_ids, n_final, counts, tau, NULL, NULL, NULL, cells);
+    return colbandit_core(&src, N, K, M, B, alpha, delta, a, b, pi, NULL, 0, 1, out_ids,
+                          out_scores, final_ids, n_final, counts, tau, NULL, NULL, NULL, cells);
 }
 
 /* ------------------------------------------------------------------ */

@@ -30,6 +30,12 @@ int oracle_colbandit_from_H(const double *H, int64_t N, int T, int K, int M, int
                             int64_t *out_ids, double *out_scores, int64_t *final_ids,
                             int64_t *n_final, int64_t *counts, double *tau, double *tr_lcb,
                             double *tr_ucb, uint8_t *tr_alive, int64_t *cells);
+int oracle_colbandit_resume(const double *H, const double *H_exact, int64_t N, int T, int K, int M,
+                            int B, double alpha, double delta, double a, double b, const int32_t *pi,
+                            const int64_t *A0, int64_t nA0, int r0, int64_t *out_ids,
+                            double *out_scores, int64_t *final_ids, int64_t *n_final, int64_t *counts,
+                            double *tau, double *tr_lcb, double *tr_ucb, uint8_t *tr_alive,
+                            int64_t *cells);
 int oracle_colbandit_coarse(const double *H_coarse, const double *H_exact, int64_t N, int T,
                             int K, int M, int B, double alpha, double delta, double a, double b,
                             const int32_t *pi, int64_t *out_ids, double *out_scores,
@@ -149,6 +155,18 @@ int main(void)
                                    out_sc2, final2, &n_final2, counts2, tau2, cells2);
     CHECK(r2 == r1 && n_final2 == n_final);
     for (int k = 0; k < K; ++k) CHECK(out_ids2[k] == out_ids[k]);
+    /* re-entered at round 2 with the first round's survivors: the same final set and top-K */
+    if (r1 >= 1) {
+        int64_t A0[N], nA0 = 0;
+        for (int i = 0; i < N; ++i)
+            if (alive[i]) A0[nA0++] = i;
+        CHECK(nA0 == counts[1]);
+        int r5 = oracle_colbandit_resume(H, NULL, N, T, K, M, B, 0.2, 0.01, -1.0, 1.0, pi, A0, nA0, 2,
+                                         out_ids2, out_sc2, final2, &n_final2, counts2, tau2, lcb,
+                                         ucb, alive, cells2);
+        CHECK(r5 == r1 && n_final2 == n_final);
+        for (int k = 0; k < K; ++k) CHECK(out_ids2[k] == out_ids[k]);
+    }
     /* alpha = 1 with every cell revealed (B = T, M = 0, K + M < N): the exhaustive top-K */
     int r3 = oracle_colbandit_from_H(H, N, T, K, 0, 1, 1.0, 0.01, -1.0, 1.0, pi, out_ids2, out_sc2,
                                      final2, &n_final2, NULL, NULL, NULL, NULL, NULL, cells2);

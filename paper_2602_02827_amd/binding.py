@@ -25,7 +25,7 @@ EXPORTS = [
     "colbandit_validate_offsets", "colbandit_strerror", "colbandit_sizeof_opts",
     "colbandit_sizeof_stats", "colbandit_quantize_i8", "colbandit_quantize_workspace_bytes",
     "colbandit_coarse_maxsim", "colbandit_doc_uniform", "colbandit_doc_uniform_workspace_bytes",
-    "colbandit_ball_carving", "colbandit_ball_carving_workspace_bytes",
+    "colbandit_ball_carving", "colbandit_ball_carving_workspace_bytes", "colbandit_cells_per_doc",
 ]
 
 
@@ -100,6 +100,8 @@ def lib():
         L.colbandit_ball_carving.restype = i
         L.colbandit_ball_carving.argtypes = [vp, i, i, i, i, vp, vp, i64, i64, i, f, vp, vp, vp, vp,
                                              vp, vp, vp, sz, vp]
+        L.colbandit_cells_per_doc.restype = i
+        L.colbandit_cells_per_doc.argtypes = [ctypes.c_double, i]
         L.colbandit_sizeof_opts.restype = sz
         L.colbandit_sizeof_opts.argtypes = []
         L.colbandit_sizeof_stats.restype = sz
@@ -241,11 +243,12 @@ def colbandit_coarse_maxsim(Q, docs_i8, docs_scale, offsets, permille=999, want_
     return {"scores": scores, "cells": cells, "q_codes": qc, "q_scales": qs}
 
 
-def cells_per_doc(gamma: float, T: int) -> int:
-    """ceil(gamma * T) of Doc-Uniform, guarded against the binary representation of gamma
-    (0.1 * 30 must give 3, not 4)."""
-    import math
-    return max(1, min(T, math.ceil(round(float(gamma) * T, 6))))
+def colbandit_cells_per_doc(gamma: float, T: int) -> int:
+    """Cells per document of Doc-Uniform at coverage gamma (computed by the library)."""
+    m = int(lib().colbandit_cells_per_doc(ctypes.c_double(gamma), int(T)))
+    if m < 0:
+        raise ColbanditError(m, "colbandit_cells_per_doc")
+    return m
 
 
 def colbandit_doc_uniform(Q, docs, offsets, K, m, seed=0, want_scores=True, want_masks=False,

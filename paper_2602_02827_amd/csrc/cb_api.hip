@@ -344,6 +344,13 @@ size_t colbandit_doc_uniform_workspace_bytes(int n_queries, int T, int d, int64_
     return uniform_layout(n_queries, T, d, N, total_tokens).total;
 }
 
+int colbandit_cells_per_doc(double gamma, int T) {
+    if (T < 1) return COLBANDIT_ERR_SHAPE;
+    if (!(gamma > 0.0) || !(gamma <= 1.0)) return COLBANDIT_ERR_KNOB;
+    const double m = ceil(gamma * (double)T - 1e-9);
+    return m < 1.0 ? 1 : (m > (double)T ? T : (int)m);
+}
+
 int colbandit_doc_uniform(const void* Q, int n_queries, int T, int d, colbandit_dtype dt,
                           const void* doc_tokens, const int64_t* doc_offsets, int64_t N,
                           int64_t total_tokens, int K, int cells_per_doc, uint64_t seed,

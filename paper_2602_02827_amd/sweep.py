@@ -79,7 +79,7 @@ def main(argv=None):
             wsu = torch.empty(int(B.lib().colbandit_doc_uniform_workspace_bytes(nq, T, d, N, total)),
                               dtype=torch.uint8, device="cuda")
             for gamma in args.gamma:
-                m = B.cells_per_doc(gamma, T)
+                m = B.colbandit_cells_per_doc(gamma, T)
                 run = lambda: B.colbandit_doc_uniform(w.Q, w.docs, w.offsets, K, m, seed=w.seed,
                                                       want_scores=False, workspace=wsu)
                 ms = timed(run)

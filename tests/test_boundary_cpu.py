@@ -193,8 +193,21 @@ def test_baseline_argument_errors(B):
     wb32 = L.colbandit_ball_carving_workspace_bytes(2, 32, 128, 0, 1000, 48000)
     assert wb16 >= base + 8 * 2 * 8 * 1000 and wb32 >= base + 4 * 2 * 32 * 128
     assert L.colbandit_ball_carving_workspace_bytes(2, 32, 128, 5, 1000, 48000) == 0
-    assert B.cells_per_doc(0.1, 30) == 3 and B.cells_per_doc(0.05, 32) == 2
-    assert B.cells_per_doc(1.0, 32) == 32 and B.cells_per_doc(0.001, 32) == 1
+
+
+def test_cells_per_doc_of_doc_uniform(B, oracle_mod):
+    """colbandit_cells_per_doc against exact rational arithmetic on the paper's gamma sweep and
+    against the oracle's separately written counterpart; error codes."""
+    from test_oracle_pins import GAMMA_SWEEP, exact_cells_per_doc
+    for g in GAMMA_SWEEP + ["0.001", "0.125", "0.3333", "0.99"]:
+        for T in range(1, 129):
+            m = B.colbandit_cells_per_doc(float(g), T)
+            assert m == exact_cells_per_doc(g, T) == oracle_mod.cells_per_doc(float(g), T), (g, T)
+    assert B.colbandit_cells_per_doc(0.1, 30) == 3 and B.colbandit_cells_per_doc(0.05, 32) == 2
+    assert B.colbandit_cells_per_doc(1.0, 32) == 32 and B.colbandit_cells_per_doc(0.001, 32) == 1
+    L = B.lib()
+    assert L.colbandit_cells_per_doc(0.0, 32) == -3 and L.colbandit_cells_per_doc(1.01, 32) == -3
+    assert L.colbandit_cells_per_doc(float("nan"), 32) == -3 and L.colbandit_cells_per_doc(0.5, 0) == -2
 
 
 def test_workspace_and_trace_sizes(B):

@@ -228,17 +228,27 @@ def test_permutation_is_valid_seeded_and_roughly_uniform(oracle_mod):
 
 
 # ---------------------------------------------------------------- Algorithm 1
-def _check_trace(oracle_mod, H, K, M, B, alpha, delta, pi, a=-1.0, b=1.0):
+def _check_trace(oracle_mod, H, K, M, B, alpha, delta, pi, a=-1.0, b=1.0, A0=None, r0=1):
     """Invariants of the elimination loop re-derived from the trace with numpy sorts and
-    library variance (Algorithm 1; Sec. 4.1-4.2; complexity paragraph)."""
+    library variance (Algorithm 1; Sec. 4.1-4.2; complexity paragraph).  A0 / r0: the loop is
+    entered at round r0 with the active set A0 (the resumed form of the oracle)."""
     N, T = H.shape
-    res = oracle_mod.colbandit_from_H(H, K, M, B, alpha, delta, pi, a, b)
+    if A0 is None:
+        res = oracle_mod.colbandit_from_H(H, K, M, B, alpha, delta, pi, a, b)
+        active = np.ones(N, bool)
+    else:
+        res = oracle_mod.colbandit_resume(H, K, M, B, alpha, delta, pi, A0, r0, a, b)
+        active = np.zeros(N, bool)
+        active[np.asarray(A0)] = True
     S = H.sum(axis=1)
-    active = np.ones(N, bool)
     cells = 0
-    n = 0
-    assert res.counts[0] == N
-    for r in range(res.rounds):
+    n = min((r0 - 1) * B, T)
+    assert res.counts[r0 - 1] == active.sum()
+    assert res.rounds >= r0 - 1
+    for r in range(r0 - 1):                                      # rounds before the entry point
+        assert np.all(np.isnan(res.lcb[r])) and np.all(np.isnan(res.ucb[r]))
+        assert not res.alive[r].any() and np.isnan(res.tau[r])
+    for r in range(r0 - 1, res.rounds):
         assert active.sum() > K + M and r * B < T            # loop condition held
         nb = min((r + 1) * B, T) - r * B
         n += nb
@@ -274,8 +284,8 @@ def _check_trace(oracle_mod, H, K, M, B, alpha, delta, pi, a=-1.0, b=1.0):
     # rescore: exact row sums; final order (score desc, id asc) over the survivors
     fin = np.flatnonzero(active)
     order = fin[np.lexsort((fin, -S[fin]))][:K]
-    np.testing.assert_array_equal(res.topk_ids, order)
-    np.testing.assert_allclose(res.topk_scores, S[order], rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(res.topk_ids[:len(order)], order)
+    np.testing.assert_allclose(res.topk_scores[:len(order)], S[order], rtol=0, atol=1e-12)
     assert res.cells_elim == cells
     assert res.cells_rescore == T * len(fin)
     assert res.cells_unique == cells + (T - n) * len(fin)
@@ -295,6 +305,67 @@ def test_elimination_loop_invariants(oracle_mod, seed):
     H = np.clip(base + rng.normal(0, 0.15, (N, T)), -1, 1)
     pi = oracle_mod.permutation(seed, 0, T)
     _check_trace(oracle_mod, H, K, M, B, alpha, 0.01, pi)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_resumed_loop_reproduces_the_uninterrupted_run(oracle_mod, seed):
+    """Entering Algorithm 1 at round r0 with the active set the uninterrupted run had there
+    gives, bit for bit, the remaining rounds, the final set and the top-K of that run: under
+    the shared reveal order the state after r0-1 rounds is the active set alone."""
+    rng = np.random.default_rng(300 + seed)
+    N = int(rng.integers(30, 250))
+    T = int(rng.choice([8, 13, 24, 32]))
+    B = int(rng.choice([1, 2, 3, 4, 5]))
+    K = int(rng.integers(1, 6))
+    M = int(rng.integers(0, 6))
+    alpha = float(rng.choice([0.2, 0.5, 1.0]))
+    H = np.clip(rng.uniform(-0.2, 0.8, (N, 1)) + rng.normal(0, 0.15, (N, T)), -1, 1)
+    pi = oracle_mod.permutation(seed, 0, T)
+    full = oracle_mod.colbandit_from_H(H, K, M, B, alpha, 0.01, pi)
+    assert full.rounds >= 1
+    for r0 in range(1, full.rounds + 2):
+        A0 = np.arange(N) if r0 == 1 else np.flatnonzero(full.alive[r0 - 2])
+        res = oracle_mod.colbandit_resume(H, K, M, B, alpha, 0.01, pi, A0, r0)
+        assert res.rounds == full.rounds
+        for r in range(r0 - 1, full.rounds):
+            np.testing.assert_array_equal(res.lcb[r], full.lcb[r])
+            np.testing.assert_array_equal(res.ucb[r], full.ucb[r])
+            np.testing.assert_array_equal(res.alive[r], full.alive[r])
+            assert res.tau[r] == full.tau[r]
+        np.testing.assert_array_equal(res.counts[r0 - 1:], full.counts[r0 - 1:])
+        np.testing.assert_array_equal(res.final_ids, full.final_ids)
+        np.testing.assert_array_equal(res.topk_ids, full.topk_ids)
+        np.testing.assert_array_equal(res.topk_scores, full.topk_scores)
+        assert res.cells_rescore == full.cells_rescore
+        n0 = min((r0 - 1) * B, T)
+        skipped = sum((min((r + 1) * B, T) - r * B) * int(full.counts[r]) for r in range(r0 - 1))
+        assert res.cells_elim == full.cells_elim - skipped and n0 <= T
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_resumed_loop_from_an_arbitrary_active_set(oracle_mod, seed):
+    """The resumed form from a state no uninterrupted run would reach (a random active set at a
+    random round), re-derived with numpy like the plain form; also the degenerate entries: an
+    active set no larger than K+M (no round runs, everything is rescored) and an entry past the
+    last batch."""
+    rng = np.random.default_rng(500 + seed)
+    N, T, B = int(rng.integers(40, 160)), int(rng.choice([12, 24, 32])), int(rng.choice([3, 4]))
+    K, M = int(rng.integers(1, 5)), int(rng.integers(0, 4))
+    H = np.clip(rng.uniform(-0.2, 0.8, (N, 1)) + rng.normal(0, 0.15, (N, T)), -1, 1)
+    pi = oracle_mod.permutation(seed, 3, T)
+    Rmax = (T + B - 1) // B
+    for r0 in (2, int(rng.integers(2, Rmax + 1)), Rmax):
+        A0 = np.sort(rng.choice(N, size=int(rng.integers(K + M + 1, N + 1)), replace=False))
+        _check_trace(oracle_mod, H, K, M, B, float(rng.choice([0.2, 1.0])), 0.01, pi, A0=A0, r0=r0)
+    small = np.sort(rng.choice(N, size=K + M, replace=False))
+    res = _check_trace(oracle_mod, H, K, M, B, 0.2, 0.01, pi, A0=small, r0=2)
+    assert res.rounds == 1 and res.cells_elim == 0
+    res = _check_trace(oracle_mod, H, K, M, B, 0.2, 0.01, pi, A0=np.arange(N), r0=Rmax + 1)
+    assert res.rounds == Rmax and res.cells_elim == 0 and res.cells_unique == 0
+    ids, _ = oracle_mod.topk(H.sum(1), K)
+    np.testing.assert_array_equal(res.topk_ids, ids)          # everything rescored: exhaustive
+    with pytest.raises(RuntimeError):                          # not ascending
+        oracle_mod.colbandit_resume(H, K, M, B, 0.2, 0.01, pi, np.array([3, 2, 9]), 2)
 
 
 def test_hand_sized_run(oracle_mod):
@@ -553,6 +624,32 @@ def test_doc_uniform_subsets_have_the_stated_size_and_are_uniform(oracle_mod):
     assert [oracle_mod.uniform_subset(7, 4, i, T, m) for i in range(50)] != masks[:50]
     assert [oracle_mod.uniform_subset(8, 3, i, T, m) for i in range(50)] != masks[:50]
     assert [oracle_mod.uniform_subset(7, 3, i, T, m) for i in range(50)] == masks[:50]
+
+
+# the paper's gamma sweep of Doc-Uniform (appendix "Compared Methods"): 0.05 steps to 0.50, then
+# 0.70, 0.80, 0.90, 1.00
+GAMMA_SWEEP = ["0.05", "0.10", "0.15", "0.20", "0.25", "0.30", "0.35", "0.40", "0.45", "0.50",
+               "0.70", "0.80", "0.90", "1.00"]
+
+
+def exact_cells_per_doc(gamma_text, T):
+    """ceil(gamma * T) in exact rational arithmetic on the decimal text of gamma."""
+    from fractions import Fraction
+    return max(1, min(T, math.ceil(Fraction(gamma_text) * T)))
+
+
+def test_doc_uniform_budget_is_the_exact_ceiling_on_the_papers_sweep(oracle_mod):
+    """ceil(gamma T) of Doc-Uniform's algorithm box, for every gamma the paper sweeps and every
+    row length up to 128, against exact rational arithmetic on the decimal gamma (0.1 * 30 is 3
+    although the double product is 3.0000000000000004; 0.15 * 20 is 3, 0.35 * 20 is 7)."""
+    for g in GAMMA_SWEEP + ["0.001", "0.125", "0.3333", "0.99"]:
+        for T in range(1, 129):
+            assert oracle_mod.cells_per_doc(float(g), T) == exact_cells_per_doc(g, T), (g, T)
+    assert oracle_mod.cells_per_doc(0.1, 30) == 3 and oracle_mod.cells_per_doc(0.35, 20) == 7
+    assert oracle_mod.cells_per_doc(0.126, 32) == 5          # 4.032: a real excess still rounds up
+    for bad in (0.0, -0.1, 1.5, float("nan")):
+        with pytest.raises(RuntimeError):
+            oracle_mod.cells_per_doc(bad, 32)
 
 
 def test_doc_uniform_generator_is_frozen(oracle_mod):
