@@ -54,7 +54,9 @@ enum {
     COLBANDIT_ERR_WORKSPACE = -5,    /* workspace or trace buffer too small           */
     COLBANDIT_ERR_ALIGNMENT = -6,    /* Q / doc_tokens / workspace misaligned         */
     COLBANDIT_ERR_HIP = -7,          /* a HIP runtime call failed                     */
-    COLBANDIT_ERR_BAD_OFFSETS = -8   /* colbandit_validate_offsets found a violation  */
+    COLBANDIT_ERR_BAD_OFFSETS = -8,  /* colbandit_validate_offsets found a violation  */
+    COLBANDIT_ERR_TOO_LARGE = -9     /* colbandit_topk_static: the sizes need more scratch
+                                        than the library's built-in buffer holds       */
 };
 
 /* Limits of this build (requests beyond them return COLBANDIT_ERR_UNSUPPORTED). */
@@ -239,6 +241,34 @@ int colbandit_topk(const void *Q, int n_queries, int T, int d, colbandit_dtype d
                    uint64_t seed, const colbandit_opts *opts, int64_t *topk_ids,
                    float *topk_scores, colbandit_stats *stats, void *workspace,
                    size_t workspace_bytes, void *stream);
+
+/*
+ * colbandit_topk for callers that cannot allocate device memory or hand over a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same computation, same kernels and same results (bit for bit) as
+ * colbandit_topk with stats == NULL, but the scratch memory is a buffer of
+ * COLBANDIT_STATIC_SCRATCH_BYTES that is part of the library's device image: every GPU the
+ * library runs on holds one copy from the first use of the library on it until the process
+ * ends.  The call allocates nothing (no hipMalloc / hipFree, no events, no host heap) and is
+ * fully asynchronous; statistics are not available here.
+ *   - Sizes whose colbandit_workspace_bytes() exceeds COLBANDIT_STATIC_SCRATCH_BYTES are
+ *     rejected with COLBANDIT_ERR_TOO_LARGE before anything is enqueued.
+ *   - The device that is current at the call is the one whose buffer is used (its address is
+ *     looked up once per device, at the first call on it; make that first call outside a
+ *     graph capture).  A failed lookup returns COLBANDIT_ERR_HIP.
+ *   - All calls on one GPU share that GPU's buffer.  A call does not rely on what an earlier
+ *     call left there (every field it reads is written by its own kernels first), but two
+ *     calls that overlap in time on one GPU - different streams, or replays of two captured
+ *     graphs at once - race on it.  Calls on one stream are ordered and safe.
+ *   - opts->trace, if given, is still the caller's own buffer.
+ * Other arguments as for colbandit_topk.
+ */
+#define COLBANDIT_STATIC_SCRATCH_BYTES (64u << 20)
+int colbandit_topk_static(const void *Q, int n_queries, int T, int d, colbandit_dtype dt,
+                          const void *doc_tokens, const int64_t *doc_offsets, int64_t N,
+                          int64_t total_tokens, int K, float alpha_ef, float delta, int M,
+                          uint64_t seed, const colbandit_opts *opts, int64_t *topk_ids,
+                          float *topk_scores, void *stream);
 
 /*
  * Doc-Uniform, the paper's static random-reveal baseline (appendix "Compared Methods",

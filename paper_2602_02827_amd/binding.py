@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libcolbandit.so")
 
 F32, BF16 = 0, 1
 MAX_ROUNDS = 64
+STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
     "colbandit_full_maxsim", "colbandit_topk", "colbandit_workspace_bytes",
@@ -26,6 +27,7 @@ EXPORTS = [
     "colbandit_sizeof_stats", "colbandit_quantize_i8", "colbandit_quantize_workspace_bytes",
     "colbandit_coarse_maxsim", "colbandit_doc_uniform", "colbandit_doc_uniform_workspace_bytes",
     "colbandit_ball_carving", "colbandit_ball_carving_workspace_bytes", "colbandit_cells_per_doc",
+    "colbandit_topk_static",
 ]
 
 
@@ -73,6 +75,9 @@ def lib():
         L.colbandit_topk.argtypes = [vp, i, i, i, i, vp, vp, i64, i64, i, f, f, i, ctypes.c_uint64,
                                      ctypes.POINTER(ColbanditOpts), vp, vp,
                                      ctypes.POINTER(ColbanditStats), vp, sz, vp]
+        L.colbandit_topk_static.restype = i
+        L.colbandit_topk_static.argtypes = [vp, i, i, i, i, vp, vp, i64, i64, i, f, f, i, ctypes.c_uint64,
+                                            ctypes.POINTER(ColbanditOpts), vp, vp, vp]
         L.colbandit_workspace_bytes.restype = sz
         L.colbandit_workspace_bytes.argtypes = [i, i, i, i64, i64, i, i]
         L.colbandit_trace_bytes.restype = sz
@@ -378,3 +383,28 @@ def colbandit_topk(Q, docs, offsets, K, alpha_ef=0.2, delta=0.01, M=5, seed=0, B
         torch.cuda.synchronize()
         tr = _parse_trace(tbuf, nq, T, Beff, N, trace_queries)
     return {"topk_ids": ids, "topk_scores": sc, "stats": st, "trace": tr}
+
+
+def colbandit_topk_static(Q, docs, offsets, K, alpha_ef=0.2, delta=0.01, M=5, seed=0, B=0, out=None,
+                          docs_i8=None, docs_scale=None):
+    """colbandit_topk on the library's built-in scratch buffer: no workspace, no statistics,
+    nothing allocated by the call (`out` supplies the two output tensors; they are created
+    here only when it is omitted).  Returns dict(topk_ids, topk_scores)."""
+    Q, nq, T, d, N, total = _shapes(Q, docs, offsets)
+    dev = docs.device
+    o = out or {}
+    ids = o.get("topk_ids") if o.get("topk_ids") is not None else \
+        torch.empty((nq, K), dtype=torch.int64, device=dev)
+    sc = o.get("topk_scores") if o.get("topk_scores") is not None else \
+        torch.empty((nq, K), dtype=torch.float32, device=dev)
+    opts = ColbanditOpts(B=B, a=0.0, b=0.0, pi=None, trace=None, trace_bytes=0, force_gather=0,
+                         no_cell_cache=0, later_rounds=0,
+                         docs_i8=None if docs_i8 is None else docs_i8.data_ptr(),
+                         docs_scale=None if docs_scale is None else docs_scale.data_ptr(),
+                         coarse_permille=0)
+    rc = lib().colbandit_topk_static(_ptr(Q), nq, T, d, _dt(Q), _ptr(docs), _ptr(offsets), N, total, K,
+                                     alpha_ef, delta, M, ctypes.c_uint64(seed & (2**64 - 1)),
+                                     ctypes.byref(opts), _ptr(ids), _ptr(sc), _stream())
+    if rc:
+        raise ColbanditError(rc, "colbandit_topk_static")
+    return {"topk_ids": ids, "topk_scores": sc}

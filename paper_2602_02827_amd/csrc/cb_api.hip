@@ -4,6 +4,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/colbandit.h"
 #include "cb_launch.h"
 
@@ -168,6 +170,31 @@ unsigned long long dense_pairs_threshold(const Problem& P, int G, bool codes) {
     return thr >= 1.8e19 ? ~0ull - 1 : (unsigned long long)thr;
 }
 
+// Scratch of colbandit_topk_static: part of the device image, one copy per GPU.  Host code
+// never uses this name as an address; it asks the runtime for the copy of the current device.
+__device__ __align__(256) unsigned char scratch[COLBANDIT_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU, once known
+std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch` (looked up once per device).
+hipError_t static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
 double rho_n(int n, int T) {
     // finite-population correction, Appendix A
     if (2 * n <= T) return 1.0 - (double)(n - 1) / (double)T;
@@ -189,6 +216,9 @@ const char* colbandit_strerror(int code) {
         case COLBANDIT_ERR_ALIGNMENT: return "pointer not aligned as required";
         case COLBANDIT_ERR_HIP: return "HIP runtime error";
         case COLBANDIT_ERR_BAD_OFFSETS: return "doc_offsets violates its preconditions";
+        case COLBANDIT_ERR_TOO_LARGE:
+            return "sizes need more scratch than the library's built-in buffer "
+                   "(COLBANDIT_STATIC_SCRATCH_BYTES): use colbandit_topk with a workspace";
         default: return "unknown error code";
     }
 }
@@ -527,12 +557,14 @@ int colbandit_full_maxsim(const void* Q, int n_queries, int T, int d, colbandit_
     return e == hipSuccess ? COLBANDIT_OK : COLBANDIT_ERR_HIP;
 }
 
-int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype dt,
-                   const void* doc_tokens, const int64_t* doc_offsets, int64_t N,
-                   int64_t total_tokens, int K, float alpha_ef, float delta, int M, uint64_t seed,
-                   const colbandit_opts* opts, int64_t* topk_ids, float* topk_scores,
-                   colbandit_stats* stats, void* workspace, size_t workspace_bytes,
-                   void* stream) {
+// Body of colbandit_topk and colbandit_topk_static.  builtin_scratch: the workspace is the
+// current device's copy of `scratch` (looked up only after every argument has passed).
+static int topk_impl(const void* Q, int n_queries, int T, int d, colbandit_dtype dt,
+                     const void* doc_tokens, const int64_t* doc_offsets, int64_t N,
+                     int64_t total_tokens, int K, float alpha_ef, float delta, int M, uint64_t seed,
+                     const colbandit_opts* opts, int64_t* topk_ids, float* topk_scores,
+                     colbandit_stats* stats, void* workspace, size_t workspace_bytes,
+                     bool builtin_scratch, void* stream) {
     int rc = check_shapes(Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens);
     if (rc) return rc;
     if (!topk_ids || !topk_scores) return COLBANDIT_ERR_NULL;
@@ -577,8 +609,13 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
     const int R = (T + kn.B - 1) / kn.B;
     if (R > COLBANDIT_MAX_ROUNDS) return COLBANDIT_ERR_UNSUPPORTED;
     const Layout L = make_layout(n_queries, T, d, N, total_tokens);
-    rc = check_workspace(workspace, workspace_bytes, L.total);
-    if (rc) return rc;
+    if (builtin_scratch) {
+        if (L.total > (size_t)COLBANDIT_STATIC_SCRATCH_BYTES) return COLBANDIT_ERR_TOO_LARGE;
+        workspace_bytes = (size_t)COLBANDIT_STATIC_SCRATCH_BYTES;
+    } else {
+        rc = check_workspace(workspace, workspace_bytes, L.total);
+        if (rc) return rc;
+    }
 
     Trace tr{};
     if (trace) {
@@ -597,6 +634,7 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
         tr.alive = (uint8_t*)b;
     }
 
+    if (builtin_scratch && static_scratch(&workspace) != hipSuccess) return COLBANDIT_ERR_HIP;
     Work W = carve(workspace, L);
     if (no_cache) W.cache_cap = 0;
     const Problem P{Q, n_queries, T, d, (int)dt, doc_tokens, doc_offsets, N, total_tokens};
@@ -703,6 +741,27 @@ int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype d
     }
     free(hist);
     return COLBANDIT_OK;
+}
+
+int colbandit_topk(const void* Q, int n_queries, int T, int d, colbandit_dtype dt,
+                   const void* doc_tokens, const int64_t* doc_offsets, int64_t N,
+                   int64_t total_tokens, int K, float alpha_ef, float delta, int M, uint64_t seed,
+                   const colbandit_opts* opts, int64_t* topk_ids, float* topk_scores,
+                   colbandit_stats* stats, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+    return topk_impl(Q, n_queries, T, d, dt, doc_tokens, doc_offsets, N, total_tokens, K, alpha_ef,
+                     delta, M, seed, opts, topk_ids, topk_scores, stats, workspace, workspace_bytes,
+                     false, stream);
+}
+
+int colbandit_topk_static(const void* Q, int n_queries, int T, int d, colbandit_dtype dt,
+                          const void* doc_tokens, const int64_t* doc_offsets, int64_t N,
+                          int64_t total_tokens, int K, float alpha_ef, float delta, int M,
+                          uint64_t seed, const colbandit_opts* opts, int64_t* topk_ids,
+                          float* topk_scores, void* stream) {
+    // stats == NULL: kernel launches only (no events, no host allocation, no read-back)
+    return topk_impl(Q, n_queries, T, d, dt, doc_tokens, doc_offsets, N, total_tokens, K, alpha_ef,
+                     delta, M, seed, opts, topk_ids, topk_scores, nullptr, nullptr, 0, true, stream);
 }
 
 }  // extern "C"

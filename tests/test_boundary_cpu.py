@@ -39,8 +39,8 @@ def test_struct_layouts_match_the_header(B):
 
 
 def test_strerror_is_defined_for_every_code(B):
-    msgs = {B.strerror(c) for c in range(0, -9, -1)}
-    assert len(msgs) == 9 and "unknown error code" not in msgs
+    msgs = {B.strerror(c) for c in range(0, -10, -1)}
+    assert len(msgs) == 10 and "unknown error code" not in msgs
     assert B.strerror(-99) == "unknown error code"
 
 
@@ -208,6 +208,31 @@ def test_cells_per_doc_of_doc_uniform(B, oracle_mod):
     L = B.lib()
     assert L.colbandit_cells_per_doc(0.0, 32) == -3 and L.colbandit_cells_per_doc(1.01, 32) == -3
     assert L.colbandit_cells_per_doc(float("nan"), 32) == -3 and L.colbandit_cells_per_doc(0.5, 0) == -2
+
+
+def test_topk_static_argument_errors_need_no_device(B):
+    """colbandit_topk_static validates like colbandit_topk and rejects sizes beyond its built-in
+    buffer before it asks the runtime for anything (so all of this runs without a GPU)."""
+    def call(**kw):
+        a = dict(Q=0x1000, nq=2, T=32, d=128, dt=1, docs=0x2000, off=0x3000, N=100, total=4000, K=5,
+                 alpha=0.2, delta=0.01, M=5, ids=0x5000, sc=0x6000, opts=None)
+        a.update(kw)
+        o = ctypes.byref(a["opts"]) if a["opts"] is not None else None
+        return B.lib().colbandit_topk_static(a["Q"], a["nq"], a["T"], a["d"], a["dt"], a["docs"], a["off"],
+                                             a["N"], a["total"], a["K"], a["alpha"], a["delta"], a["M"],
+                                             ctypes.c_uint64(0), o, a["ids"], a["sc"], None)
+    assert call(Q=None) == -1 and call(ids=None) == -1
+    assert call(K=0) == -2 and call(K=101) == -2 and call(nq=0) == -2
+    assert call(alpha=0.0) == -3 and call(delta=1.0) == -3 and call(M=-1) == -3
+    assert call(d=100) == -4 and call(opts=B.ColbanditOpts(B=17)) == -4
+    assert call(Q=0x1004) == -6
+    # the benchmark's sizes need 2.3 GB of scratch: far beyond the built-in 64 MiB
+    assert call(nq=128, N=500000, total=53040331) == -9
+    assert "COLBANDIT_STATIC_SCRATCH_BYTES" in B.strerror(-9)
+    hdr = open(os.path.join(ROOT, "include", "colbandit.h")).read()
+    assert "#define COLBANDIT_STATIC_SCRATCH_BYTES (64u << 20)" in hdr and B.STATIC_SCRATCH_BYTES == 64 << 20
+    # the largest sizes that fit are accepted by the size check of the workspace query
+    assert B.colbandit_workspace_bytes(8, 32, 128, 6000, 640000) <= B.STATIC_SCRATCH_BYTES
 
 
 def test_workspace_and_trace_sizes(B):
