@@ -25,12 +25,43 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dense Full-MaxSim kernel on the default workload, from the two
-# counter runs summarised in profiles/k_dense_C3_hbm_traffic.md (FETCH_SIZE + WRITE_SIZE, each
-# scaled by the same counter's reading for the 1 GiB calibration copy below).  Reported only
-# when the run is that workload.
-MEASURED_TRAFFIC_BYTES = {("C3-large-text-bf16", 128, 500000, 53040331): 15.43e9}
+# HBM bytes per launch of the dominant kernels come from hardware-counter runs of this very
+# command (FETCH_SIZE, then WRITE_SIZE, each scaled by the same counter's reading for the 1 GiB
+# calibration copy below).  Their summary, profiles/hbm_traffic_counters.txt, records for every
+# kernel the raw readings, the calibration factors, the workload and a hash of the kernel sources
+# it was taken from; the figure is reported only when workload and hash match this run, else null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
+KERNEL_SOURCES = ["cb_dense.hip", "cb_kernels.hip", "cb_device.h", "cb_launch.h"]
 CALIBRATION_COPY_BYTES = 1 << 30
+
+
+def kernel_source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2602_02827_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload_key):
+    """{kernel label: HBM bytes per launch} from the counter summary, or {} if it was taken on
+    other kernel sources or another workload.  Line format of the file:
+    record <label> workload=<key> sources=<hash> fetch_kib=<x> write_kib=<y> fetch_scale=<a> write_scale=<b>"""
+    out = {}
+    if not os.path.exists(TRAFFIC_FILE):
+        return out
+    have = kernel_source_hash()
+    for line in open(TRAFFIC_FILE):
+        f = line.split()
+        if len(f) < 3 or f[0] != "record":
+            continue
+        kv = dict(x.split("=", 1) for x in f[2:])
+        if kv.get("workload") != workload_key or kv.get("sources") != have:
+            continue
+        out[f[1]] = 1024.0 * (float(kv["fetch_kib"]) * float(kv["fetch_scale"]) +
+                              float(kv["write_kib"]) * float(kv["write_scale"]))
+    return out
 
 
 def main():
@@ -46,6 +77,7 @@ def main():
     ap.add_argument("--no-int8", action="store_true", help="skip the int8 coarse-pass leg")
     ap.add_argument("--no-baselines", action="store_true",
                     help="skip the Doc-Uniform / Ball-carving operating points")
+    ap.add_argument("--no-k10", action="store_true", help="skip the K = 10 leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-docs", type=int, default=60000)
     args = ap.parse_args()
@@ -192,6 +224,42 @@ def main():
                 "corpus_codes_gb": round(total * d / 1e9, 2)}
         del d8
 
+    # the configuration's second setting, K = 10 (same corpus, same knobs otherwise)
+    k10 = None
+    if args.K != 10 and N > 15 and not args.no_k10:
+        K10 = 10
+        out10 = {"topk_ids": torch.empty((nq, K10), dtype=torch.int64, device=dev),
+                 "topk_scores": torch.empty((nq, K10), dtype=torch.float32, device=dev)}
+        f10 = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K10, workspace=ws, want_scores=False, out=dict(out10))
+
+        def run_cb10(stats=False):
+            return B.colbandit_topk(w.Q, w.docs, w.offsets, K10, alpha, delta, M, w.seed, workspace=ws,
+                                    want_stats=stats)
+
+        for _ in range(max(1, args.warmup)):
+            run_cb10()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            run_cb10()
+        e1.record()
+        torch.cuda.synchronize()
+        ms10 = e0.elapsed_time(e1) / args.steps
+        r10 = run_cb10(stats=True)
+        torch.cuda.synchronize()
+        idf, idc = f10["topk_ids"].cpu().numpy(), r10["topk_ids"].cpu().numpy()
+        st10 = r10["stats"]
+        k10 = {"K": K10, "ms": round(ms10, 3), "queries_per_s": round(nq / (ms10 * 1e-3), 1),
+               "effective_cells_per_s": round(cells_total / (ms10 * 1e-3), 1),
+               "coverage": round(float(sum(s["cells_unique"] for s in st10)) / cells_total, 4),
+               "overlap_at_k": round(float(np.mean([len(set(idf[q]) & set(idc[q])) / K10 for q in range(nq)])), 4),
+               "mean_rounds": round(float(np.mean([s["rounds"] for s in st10])), 2),
+               "speedup_vs_full": round(ms_full / ms10, 2),
+               "survivor_scores_bit_identical_to_full": bool(torch.equal(
+                   r10["topk_scores"], torch.gather(out_full["scores"], 1, r10["topk_ids"].clamp(min=0))))}
+        del f10, r10
+
     # the paper's two non-adaptive baselines at one operating point each (appendix "Compared
     # Methods"): Doc-Uniform at Col-Bandit's own coverage, Ball-carving at tau = 0.8; reported
     # beside the step, not part of `value`
@@ -237,42 +305,70 @@ def main():
     ms_dense = float(np.mean([m[0] for m in ms_kernel]))
     ms_topk = float(np.mean([m[1] for m in ms_kernel]))
     tflops_kernel = flops_full / (ms_dense * 1e-3) / 1e12
-    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, nq, N, total))
+    traffic = measured_traffic("%s/nq%d/N%d/tok%d" % (w.name, nq, N, total))
     dense = w.dtype == "bf16"
+    elem = 2 if dense else 4
     roofline = {"bound": "mfma" if dense else "alu",
                 "kernel": "k_dense (Full-MaxSim scoring kernel, bf16 16x16x32 MFMA)" if dense
                           else "k_gather (fp32 inputs)",
                 "achieved": round(tflops_kernel, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(tflops_kernel / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                "frac": round(tflops_kernel / PEAK_BF16_TFLOPS, 4), "traffic": traffic.get("full_maxsim"),
                 "ms_per_launch": round(ms_dense, 3),
                 "flops_per_launch": flops_full,
                 "note": "algorithmic flops 2*T*d per (query, document token) x nq x tokens per "
-                        "launch, over the kernel's own duration taken by the library with "
-                        "events on the launch stream inside the timed steps; the whole call "
-                        "(kernel + chunk table + top-K, %.3f ms) runs at %.1f TFLOP/s"
+                        "launch, over the kernel's own duration taken by the library with events "
+                        "on the launch stream inside the timed steps; the whole call (kernel + "
+                        "chunk table + top-K, %.3f ms) runs at %.1f TFLOP/s; traffic = HBM bytes "
+                        "per launch from hardware counters (profiles/hbm_traffic_counters.txt), "
+                        "null unless taken on these kernel sources and this workload"
                         % (ms_full, tflops)}
 
-    # the gathered rounds (rounds >= 2) against the HBM roofline: every document that survives
-    # round 1 is streamed once (visit-once cell cache), so the algorithmic bytes are the
-    # survivors' tokens; their mean length is taken as the corpus mean (the exact ids stay on
-    # the device)
-    pairs2 = float(sum(s["survivors"][1] for s in st if s["rounds"] >= 2))
-    gather_bytes = pairs2 * (total / float(N)) * d * 2
-    ms_later = st[0]["ms_later_reveals"]
-    # if a later round streamed the corpus instead of gathering, or the queries' survivors
-    # overlap so much that most gathered bytes come from cache, the estimate does not hold
-    gather_valid = ms_later > 0 and not st[0]["corpus_pass_rounds"] and \
-        pairs2 * (total / float(N)) <= 4 * total
-    gather = {"bound": "hbm", "kernel": "k_gather (rounds >= 2, visit-once cell cache)",
-              "achieved": round(gather_bytes / (ms_later * 1e-3) / 1e9, 1) if gather_valid else None,
-              "peak": PEAK_HBM_GBS, "unit": "GB/s",
-              "frac": round(gather_bytes / (ms_later * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if gather_valid else None,
-              "pairs": pairs2, "ms": round(ms_later, 3),
+    # round 1 of Col-Bandit: one pass over the whole corpus that multiplies B query rows per query.
+    # Two bounds apply, HBM (the corpus once + the (sum, M2) pair of every (query, document)) and the
+    # matrix pipes (2*B*d flops per (query, token)); the larger lower bound on the time is the binding one
+    ms_r1 = st[0]["ms_first_reveal"]
+    nb1 = min(w.B, T)
+    bytes_r1 = float(total) * d * elem + 8.0 * nq * N
+    flops_r1 = 2.0 * nq * nb1 * d * total
+    t_hbm, t_mfma = bytes_r1 / (PEAK_HBM_GBS * 1e9), flops_r1 / (PEAK_BF16_TFLOPS * 1e12)
+    reveal1 = {"kernel": "k_dense<..., REVEAL> (round-1 reveal, corpus-streaming)",
+               "ms": round(ms_r1, 3),
+               "bound": "mfma" if t_mfma >= t_hbm else "hbm",
+               "frac": round(max(t_hbm, t_mfma) * 1e3 / ms_r1, 4) if ms_r1 > 0 else None,
+               "hbm": {"achieved": round(bytes_r1 / (ms_r1 * 1e-3) / 1e9, 1) if ms_r1 > 0 else None,
+                       "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                       "frac": round(t_hbm * 1e3 / ms_r1, 4) if ms_r1 > 0 else None,
+                       "bytes": bytes_r1, "traffic": traffic.get("reveal_round1")},
+               "mfma": {"achieved": round(flops_r1 / (ms_r1 * 1e-3) / 1e12, 1) if ms_r1 > 0 else None,
+                        "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(t_mfma * 1e3 / ms_r1, 4) if ms_r1 > 0 else None,
+                        "flops": flops_r1},
+               "note": "ms = the whole first-reveal phase of the statistics call (k_init, chunk table "
+                       "and the reveal kernel; events on the launch stream); frac = the larger of the "
+                       "two lower bounds on the time over the measured time"} if dense else None
+
+    # round 2 against the HBM roofline: every (query, document) pair that survives round 1 is
+    # streamed once (visit-once cell cache).  Bytes = the tokens of exactly those documents, added
+    # up on the device by the prune kernel; ms = the reveal launches of round 2 alone.  The figure
+    # over all rounds >= 2 (which adds the launches that find nothing left to gather) is given too.
+    pairs2 = float(st[0]["pairs_round2"])
+    gather_bytes = float(st[0]["tokens_round2"]) * d * elem
+    ms_r2, ms_later = st[0]["ms_reveal_round2"], st[0]["ms_later_reveals"]
+    # if round 2 streamed the corpus instead of gathering, or the queries' survivors overlap so
+    # much that most gathered bytes come from cache, HBM is not the bound
+    gather_valid = ms_r2 > 0 and 2 not in st[0]["corpus_pass_rounds"] and gather_bytes <= 4.0 * total * d * elem
+    gbs = lambda ms: round(gather_bytes / (ms * 1e-3) / 1e9, 1) if gather_valid and ms > 0 else None
+    gather = {"bound": "hbm", "kernel": "k_gather (round 2: reveal + cell cache fill)",
+              "achieved": gbs(ms_r2), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+              "frac": round(gbs(ms_r2) / PEAK_HBM_GBS, 4) if gather_valid else None,
+              "traffic": traffic.get("gather_round2"),
+              "pairs": pairs2, "bytes": gather_bytes, "ms": round(ms_r2, 3),
+              "all_rounds_ge2": {"ms": round(ms_later, 3), "achieved": gbs(ms_later)},
               "corpus_pass_rounds": st[0]["corpus_pass_rounds"],
-              "note": "bytes = (query, document) pairs entering round 2 x mean document bytes; "
-                      "ms = all reveal launches of rounds >= 2 (events, statistics call); null "
-                      "when a later round took the corpus pass or the gathered bytes exceed 4x "
-                      "the corpus (then caches serve most of them and HBM is not the bound)"}
+              "note": "bytes = document tokens of the (query, document) pairs that entered round 2 x "
+                      "row bytes (summed on the device); ms = the reveal launches of round 2 (events, "
+                      "statistics call); null when round 2 took the corpus pass or the gathered bytes "
+                      "exceed 4x the corpus (then caches serve most of them and HBM is not the bound)"}
 
     line = {
         "metric": "queries/s through one step = Full-MaxSim top-K + Col-Bandit top-K at N=%d,T=%d,"
@@ -283,7 +379,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "recipe": w.recipe, "n_queries": nq, "N": N, "T": T, "d": d,
-                   "total_tokens": total, "K": K, "alpha_ef": alpha, "delta": delta, "M": M, "B": w.B},
+                   "total_tokens": total, "K": K, "alpha_ef": alpha, "delta": delta, "M": M, "B": w.B,
+                   "workspace_bytes": int(ws.numel()), "corpus_bytes": int(total) * d * elem},
         "full_maxsim": {"ms": round(ms_full, 3), "queries_per_s": round(nq / (ms_full * 1e-3), 1),
                         "cells_per_s": round(cells_total / (ms_full * 1e-3), 1),
                         "tflops": round(tflops, 2), "ms_scoring_kernel": round(ms_dense, 3),
@@ -291,7 +388,9 @@ def main():
         "colbandit": {"ms": round(ms_cb, 3), "queries_per_s": round(nq / (ms_cb * 1e-3), 1),
                       "revealed_cells_per_s": round(cells_touched / (ms_cb * 1e-3), 1),
                       "effective_cells_per_s": round(cells_total / (ms_cb * 1e-3), 1),
-                      "coverage": round(coverage, 4), "overlap_at_k": round(overlap, 4),
+                      "coverage": round(coverage, 4),
+                      "computed_cells_over_all_cells": round(float(sum(s["cells_computed"] for s in st)) / cells_total, 4),
+                      "overlap_at_k": round(overlap, 4),
                       "overlap_at_k_within_score_tolerance": round(overlap_tol, 4),
                       "mean_rounds": round(float(np.mean(rounds)), 2),
                       "mean_survivors_after_round1": round(surv1, 1),
@@ -301,9 +400,11 @@ def main():
                                     ("ms_first_reveal", "ms_later_reveals", "ms_select_prune",
                                      "ms_rescore_topk")},
                       "survivor_scores_bit_identical_to_full": same_bits},
+        "colbandit_k10": k10,
         "colbandit_int8": int8,
         "baselines": baselines,
         "roofline": roofline,
+        "roofline_reveal1": reveal1,
         "roofline_gather": gather,
         "paper_context": "paper (CPU, real embeddings): up to ~8x fewer MaxSim FLOPs, up to ~13x "
                          "single-thread CPU speedup at Overlap@5 >= 0.9; no GPU kernel reported",
@@ -315,8 +416,9 @@ def main():
         nthreads = oracle.num_threads()
         nq_s = min(nq, nthreads)
         n_s = min(N, args.cpu_sample_docs)
-        off = w.offsets[: n_s + 1].cpu().numpy()
-        E = w.docs[: int(off[-1])].float().cpu().numpy()
+        # a seeded uniform sample of the documents (in index order), not a prefix of the corpus
+        sample = np.sort(np.random.default_rng(2602).choice(N, size=n_s, replace=False))
+        E, off = w.host_docs(sample.tolist())
         Qh = w.host_queries(list(range(nq_s)))
         pi = np.stack([oracle.permutation(w.seed, q, T) for q in range(nq_s)])
         t0 = time.perf_counter()
@@ -336,7 +438,7 @@ def main():
         line["cpu_baseline"] = {
             "value": round(nq_s / (t_full + t_cb) * scale, 5), "unit": "queries/s",
             "cores": nthreads, "kind": "oracle",
-            "sample": "%d queries x first %d documents of the same corpus, one thread per query; "
+            "sample": "%d queries x a seeded uniform sample of %d documents of the same corpus, one thread per query; "
                       "%.1f s Full + %.1f s Col-Bandit measured, rate scaled by %d/%d to the full N"
                       % (nq_s, n_s, t_full, t_cb, n_s, N),
             "full_s": round(t_full, 2), "colbandit_s": round(t_cb, 2),

@@ -122,11 +122,27 @@ typedef struct {
     float ms_rescore_topk;                            /* rescore and final top-K
                                                          (cf. the paper's stage split in
                                                          its overhead-breakdown table)  */
-    uint32_t pad0;
+    float ms_reveal_round2;                           /* of ms_later_reveals: the reveal
+                                                         launches of round 2 alone          */
     uint64_t corpus_pass_rounds;                      /* bit r-1 set: the batch revealed
                                                          round r (r >= 2) by one pass over
                                                          the corpus instead of per-pair
                                                          gathers (same for all queries)  */
+    int64_t cells_computed;                           /* cells the kernels COMPUTED for this
+                                                         query, which can exceed the cells
+                                                         revealed to the bounds: a corpus
+                                                         pass computes a round's batch for
+                                                         all N documents, the first gathered
+                                                         round of a list that fits the cell
+                                                         cache computes all T cells of its
+                                                         documents once (later rounds and
+                                                         the rescore then compute none)   */
+    uint64_t pairs_round2;                            /* (query, document) pairs of the whole
+                                                         batch that entered round 2 still
+                                                         held as document ids, and           */
+    uint64_t tokens_round2;                           /* the document tokens of those pairs:
+                                                         what a gathered round 2 has to
+                                                         read (same for all queries)       */
 } colbandit_stats;
 
 /* sizeof(colbandit_opts) / sizeof(colbandit_stats) as this library was compiled: lets a

@@ -46,7 +46,9 @@ class ColbanditStats(ctypes.Structure):
                 ("cells_unique", ctypes.c_int64), ("ms_total", ctypes.c_float),
                 ("ms_first_reveal", ctypes.c_float), ("ms_later_reveals", ctypes.c_float),
                 ("ms_select_prune", ctypes.c_float), ("ms_rescore_topk", ctypes.c_float),
-                ("pad0", ctypes.c_uint32), ("corpus_pass_rounds", ctypes.c_uint64)]
+                ("ms_reveal_round2", ctypes.c_float), ("corpus_pass_rounds", ctypes.c_uint64),
+                ("cells_computed", ctypes.c_int64), ("pairs_round2", ctypes.c_uint64),
+                ("tokens_round2", ctypes.c_uint64)]
 
 
 class ColbanditError(RuntimeError):
@@ -376,6 +378,8 @@ def colbandit_topk(Q, docs, offsets, K, alpha_ef=0.2, delta=0.01, M=5, seed=0, B
                "cells_unique": s.cells_unique, "ms_total": s.ms_total,
                "ms_first_reveal": s.ms_first_reveal, "ms_later_reveals": s.ms_later_reveals,
                "ms_select_prune": s.ms_select_prune, "ms_rescore_topk": s.ms_rescore_topk,
+               "ms_reveal_round2": s.ms_reveal_round2, "cells_computed": s.cells_computed,
+               "pairs_round2": s.pairs_round2, "tokens_round2": s.tokens_round2,
                "corpus_pass_rounds": [r + 1 for r in range(64) if (s.corpus_pass_rounds >> r) & 1]}
               for s in stats]
     tr = None

@@ -41,7 +41,7 @@ Layout make_layout(int nq, int T, int d, int64_t N, int64_t total_tokens) {
     L.list1 = take(4 * qn);
     L.stat = take(8 * qn);
     L.stat2 = take(8 * qn);
-    L.pairs = take(8 * (size_t)(COLBANDIT_MAX_ROUNDS + 4));
+    L.pairs = take(8 * 2 * (size_t)(COLBANDIT_MAX_ROUNDS + 4));
     L.seg_cnt = take(4 * (size_t)nq * 64);
     L.rescored = take(4 * qn);
     L.scores = take(4 * qn);
@@ -115,7 +115,8 @@ int check_workspace(const void* ws, size_t bytes, size_t need) {
 }
 
 // Phase timing for colbandit_stats: one HIP event per phase boundary on the call's stream.
-enum { PH_FIRST_REVEAL = 0, PH_LATER_REVEAL = 1, PH_SELECT = 2, PH_RESCORE = 3, PH_COUNT = 4 };
+enum { PH_FIRST_REVEAL = 0, PH_LATER_REVEAL = 1, PH_SELECT = 2, PH_RESCORE = 3, PH_ROUND2_REVEAL = 4,
+       PH_COUNT = 5 };
 struct PhaseTimer {
     static constexpr int kMax = 4 * (COLBANDIT_MAX_ROUNDS + 4);
     hipEvent_t ev[kMax];
@@ -682,8 +683,8 @@ static int topk_impl(const void* Q, int n_queries, int T, int d, colbandit_dtype
             if (e == hipSuccess) e = launch_gather_reveal(P, W, rr, co, st);
             if (e == hipSuccess && r >= 2) e = launch_gather_cells(P, W, rr, co, st);
         }
-        pt.mark(r == 1 ? PH_FIRST_REVEAL : PH_LATER_REVEAL);
-        if (e == hipSuccess) e = launch_select_prune(P, W, kn, rr, tr, st);
+        pt.mark(r == 1 ? PH_FIRST_REVEAL : (r == 2 ? PH_ROUND2_REVEAL : PH_LATER_REVEAL));
+        if (e == hipSuccess) e = launch_select_prune(P, W, kn, rr, R, tr, st);
         pt.mark(PH_SELECT);
     }
     // exact rescore from the stored embeddings; cached cells give it only when they are exact
@@ -702,16 +703,16 @@ static int topk_impl(const void* Q, int n_queries, int T, int d, colbandit_dtype
     int32_t* hist = (int32_t*)malloc(sizeof(int32_t) * nh);
     if (!hist) { pt.destroy(); return COLBANDIT_ERR_HIP; }
     hipError_t ce = hipMemcpyAsync(hist, W.cnt_hist, sizeof(int32_t) * nh, hipMemcpyDeviceToHost, st);
-    unsigned long long pairs_h[COLBANDIT_MAX_ROUNDS + 2];
+    unsigned long long pairs_h[2 * (COLBANDIT_MAX_ROUNDS + 2)];
     if (ce == hipSuccess)
-        ce = hipMemcpyAsync(pairs_h, W.pairs, sizeof(unsigned long long) * (size_t)(R + 2),
+        ce = hipMemcpyAsync(pairs_h, W.pairs, sizeof(unsigned long long) * 2 * (size_t)(R + 2),
                             hipMemcpyDeviceToHost, st);
     if (ce == hipSuccess) ce = hipStreamSynchronize(st);
     // the rounds whose device-side test took the corpus pass (the same test as the kernels')
     uint64_t corpus_rounds = 0;
     for (int r = 2; ce == hipSuccess && loop && r <= R; ++r)
         if (round_thr[r] != ~0ull && pairs_h[r] > round_thr[r]) corpus_rounds |= 1ull << (r - 1);
-    float ms = 0.f, phase_ms[PH_COUNT] = {0.f, 0.f, 0.f, 0.f};
+    float ms = 0.f, phase_ms[PH_COUNT] = {0.f, 0.f, 0.f, 0.f, 0.f};
     if (ce == hipSuccess) pt.collect(phase_ms, ms);
     pt.destroy();
     if (ce != hipSuccess) { free(hist); return COLBANDIT_ERR_HIP; }
@@ -721,9 +722,21 @@ static int topk_impl(const void* Q, int n_queries, int T, int d, colbandit_dtype
         s.survivors[0] = (int32_t)N;
         int64_t count = N;
         int n = 0, r = 0;
+        bool cached = false;        // the query's list holds cache slots (its cells are cached)
         while (loop && count > (int64_t)K + M && r * kn.B < T) {   // the loop condition of Algorithm 1
             const int lo = r * kn.B, hi = (r + 1) * kn.B < T ? (r + 1) * kn.B : T;
             s.cells_elim += (int64_t)(hi - lo) * count;
+            // cells COMPUTED for this round: a corpus pass (round 1 always covers all N documents)
+            // computes the batch for every document; the first gathered round of a list that fits
+            // the cache computes all T cells of its documents once, later rounds read them back
+            const bool pass = r == 0 || ((corpus_rounds >> r) & 1ull);
+            if (!cached) {
+                if (pass) s.cells_computed += (int64_t)(hi - lo) * N;
+                else if (W.cache_cap > 0 && count <= W.cache_cap) {
+                    s.cells_computed += (int64_t)T * count;
+                    cached = true;
+                } else s.cells_computed += (int64_t)(hi - lo) * count;
+            }
             n = hi;
             ++r;
             count = hist[(size_t)r * n_queries + q];
@@ -732,12 +745,16 @@ static int topk_impl(const void* Q, int n_queries, int T, int d, colbandit_dtype
         s.rounds = r;
         s.cells_rescore = (int64_t)T * count;
         s.cells_unique = s.cells_elim + (int64_t)(T - n) * count;
+        if (!cached || co) s.cells_computed += (int64_t)T * count;   // the rescore gathers the survivors
         s.ms_total = ms;
         s.ms_first_reveal = phase_ms[PH_FIRST_REVEAL];
-        s.ms_later_reveals = phase_ms[PH_LATER_REVEAL];
+        s.ms_later_reveals = phase_ms[PH_LATER_REVEAL] + phase_ms[PH_ROUND2_REVEAL];
+        s.ms_reveal_round2 = phase_ms[PH_ROUND2_REVEAL];
         s.ms_select_prune = phase_ms[PH_SELECT];
         s.ms_rescore_topk = phase_ms[PH_RESCORE];
         s.corpus_pass_rounds = corpus_rounds;
+        s.pairs_round2 = R >= 2 ? pairs_h[2] : 0ull;
+        s.tokens_round2 = R >= 2 ? pairs_h[(R + 2) + 2] : 0ull;
     }
     free(hist);
     return COLBANDIT_OK;

@@ -22,7 +22,7 @@ __global__ void k_init(QueryCtl* ctl, int32_t* pi, const int32_t* user_pi, int32
                        int32_t* tr_count, float* tr_tau, unsigned long long* pairs) {
     const int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q == 0)
-        for (int r = 0; r <= R + 1; ++r) pairs[r] = 0ull;
+        for (int r = 0; r < 2 * (R + 2); ++r) pairs[r] = 0ull;   // pair counts, then their token counts
     if (q >= nq) return;
     QueryCtl c;
     c.count = (int)N;
@@ -183,27 +183,53 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
     }
 
     const int stride = gridDim.x * 4;
-    for (int k = first; k < count; k += stride) {
-        int id = list ? list[k] : k;
+    // entry k of the list -> document id and its token range (clamped into the corpus)
+    auto pair_of = [&](int k, int& id, int64_t& o0, int64_t& o1) {
+        id = list ? list[k] : k;
         if (slot_ids) id = slot_ids[id];
-        int64_t o0 = A.off[id], o1 = A.off[id + 1];
+        o0 = A.off[id];
+        o1 = A.off[id + 1];
         o0 = o0 < 0 ? 0 : (o0 > A.total ? A.total : o0);
         o1 = o1 < o0 ? o0 : (o1 > A.total ? A.total : o1);
+    };
+    // one block of 16 token rows starting at r0 (rows past the document's end repeat its last token)
+    auto load_rows = [&](F& a, int64_t r0, int64_t o1) {
+        int64_t row = r0 + col;
+        row = row < o1 ? row : o1 - 1;
+        a.load((const char*)A.docs + (size_t)row * row_bytes, kg);
+    };
+    int id;
+    int64_t o0, o1;
+    pair_of(first, id, o0, o1);
+    for (int k = first; k < count; k += stride) {
+        // The next pair's list entry and offsets are requested now and used after this pair's
+        // blocks, and two token blocks are kept in flight: a gathered document is a chain of
+        // dependent memory latencies (entry -> offsets -> tokens), which this hides.
+        int id_n = id;
+        int64_t o0_n = o0, o1_n = o1;
+        if (k + stride < count) pair_of(k + stride, id_n, o0_n, o1_n);
 
         V h[TQ];
 #pragma unroll
         for (int tt = 0; tt < TQ; ++tt) h[tt] = lowest_val<V>();
 
-        for (int64_t r0 = o0; r0 < o1; r0 += 16) {
-            int64_t row = r0 + col;
-            row = row < o1 ? row : o1 - 1;
-            F a;
-            a.load((const char*)A.docs + (size_t)row * row_bytes, kg);
+        auto fold_block = [&](const F& a) {
 #pragma unroll
             for (int tt = 0; tt < TQ; ++tt) {
                 typename F::acc_t acc = {0, 0, 0, 0};
                 F::mma(acc, a, bq[tt]);
                 h[tt] = fold_max(h[tt], acc);
+            }
+        };
+        F a0, a1;
+        if (o0 < o1) load_rows(a0, o0, o1);
+        if (o0 + 16 < o1) load_rows(a1, o0 + 16, o1);
+        for (int64_t r0 = o0; r0 < o1; r0 += 32) {
+            fold_block(a0);
+            if (r0 + 32 < o1) load_rows(a0, r0 + 32, o1);
+            if (r0 + 16 < o1) {
+                fold_block(a1);
+                if (r0 + 48 < o1) load_rows(a1, r0 + 48, o1);
             }
         }
 
@@ -272,6 +298,9 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
                 }
             }
         }
+        id = id_n;
+        o0 = o0_n;
+        o1 = o1_n;
     }
 }
 
@@ -660,7 +689,9 @@ struct SelArgs {
     int32_t* list1;
     float2* stat;
     const float2* stat2;
-    unsigned long long* pairs;           // [R+2]
+    unsigned long long* pairs;           // [R+2] pairs, then [R+2] document tokens of those pairs
+    const int64_t* off;                  // document offsets (token counts of the kept pairs)
+    int R;
     unsigned long long dense_thr;        // ~0: this round cannot be a dense one
     int64_t N;
     int nq, T, K, KM;
@@ -718,6 +749,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
     __shared__ uint32_t hist[2048];
     __shared__ int pick[2];
     __shared__ int wtot[SEL_WAVES];
+    __shared__ unsigned long long kept_tokens;
     const int q = blockIdx.x;
     const QueryCtl c = A.ctl[q];
     if (!c.active) {
@@ -739,6 +771,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
     const int32_t* cid = A.cid + (size_t)q * A.cache_cap;
     const int n = A.n, T = A.T;
     const float kappa = A.kappa, a = A.a, b = A.b;
+    if (threadIdx.x == 0) kept_tokens = 0ull;       // published by the barriers of the passes below
+    long long my_tokens = 0;                        // tokens of the documents this thread keeps
 
     if (c.mode == 1) {          // fold this round's batch in from the cached cells
         float2* cst = A.cstat + (size_t)q * A.cache_cap;
@@ -835,7 +869,12 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
                 int pos = base + block_excl_scan(__popc(keep), wtot, total);
 #pragma unroll
                 for (int u = 0; u < ITEMS; ++u)
-                    if (keep & (1u << u)) outl[pos++] = e[u];
+                    if (keep & (1u << u)) {
+                        outl[pos++] = e[u];
+                        // the final pass over document ids also adds up what a gather of the
+                        // survivors would have to read
+                        if (trace_kept && !slots) my_tokens += A.off[e[u] + 1] - A.off[e[u]];
+                    }
                 base += total;
             }
 #pragma unroll
@@ -929,6 +968,13 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
     }
     const float tau = key_float(tkey);
     const int base = filter(std::integral_constant<int, SEL_ITEMS>{}, sel_in, sel_count, out, tau, true);
+    if (!slots) {                       // uniform over the workgroup
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) my_tokens += __shfl_down(my_tokens, o);
+        if ((threadIdx.x & 63) == 0 && my_tokens != 0)
+            atomicAdd(&kept_tokens, (unsigned long long)my_tokens);
+        __syncthreads();
+    }
 
     if (threadIdx.x == 0) {
         QueryCtl nc;
@@ -940,7 +986,10 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_prune(SelArgs A) {
         nc.pad0 = nc.pad1 = nc.pad2 = 0;
         A.ctl[q] = nc;
         // what the next round would have to gather: the active sets still held as ids
-        if (nc.active && nc.mode == 0) atomicAdd(A.pairs + A.r + 1, (unsigned long long)base);
+        if (nc.active && nc.mode == 0) {
+            atomicAdd(A.pairs + A.r + 1, (unsigned long long)base);
+            atomicAdd(A.pairs + (A.R + 2) + A.r + 1, kept_tokens);
+        }
         A.cnt_hist[A.r * A.nq + q] = base;
         A.tau_hist[(A.r - 1) * A.nq + q] = tau;
         if (A.tr_count) {
@@ -1105,7 +1154,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_segments(SelArgs A) {
 }
 
 hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
-                               const RevealRound& rr, const Trace& tr, hipStream_t st) {
+                               const RevealRound& rr, int R, const Trace& tr, hipStream_t st) {
     SelArgs A{};
     A.ctl = W.ctl;
     A.list0 = W.list[0];
@@ -1113,6 +1162,8 @@ hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
     A.stat = W.stat;
     A.stat2 = W.stat2;
     A.pairs = W.pairs;
+    A.off = P.off;
+    A.R = R;
     A.dense_thr = rr.dense_thr;
     A.N = P.N;
     A.nq = P.nq;

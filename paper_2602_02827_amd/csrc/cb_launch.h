@@ -23,7 +23,8 @@ struct Work {
     int32_t* list[2];     // [nq][N] each: ids of the active set, ascending
     float2* stat;         // [nq][N] per (query, doc): revealed sum, centred sum of squares
     float2* stat2;        // [nq][N] batch (sum, centred squares) of a later round's dense pass
-    unsigned long long* pairs;   // [R+2] pairs[r]: (query, doc) pairs round r would have to gather
+    unsigned long long* pairs;   // [R+2] pairs[r]: (query, doc) pairs round r would have to gather;
+                                 // then [R+2]: the document tokens of those pairs
     int32_t* seg_cnt;     // [nq][64] candidates per segment of a segmented pre-filter
     float* rescored;      // [nq][N] exact score of the k-th survivor
     float* scores;        // [nq][N] Full-MaxSim scores when the caller keeps none
@@ -114,8 +115,9 @@ hipError_t launch_dense_reveal_later(const Problem& P, const Work& W, int chunk_
                                      hipStream_t st);
 bool dense_supported(const Problem& P, const Coarse* co);
 
+// R: number of rounds of the call (layout of W.pairs).
 hipError_t launch_select_prune(const Problem& P, const Work& W, const Knobs& kn,
-                               const RevealRound& rr, const Trace& tr, hipStream_t st);
+                               const RevealRound& rr, int R, const Trace& tr, hipStream_t st);
 
 // Top-K of `vals` per query.  use_ctl: candidates are the active set (vals indexed by
 // list position); else all N documents (vals indexed by id).

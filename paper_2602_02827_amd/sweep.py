@@ -1,6 +1,7 @@
 """Knob sweeps of the two scoring paths on one synthetic configuration.
 
     python -m paper_2602_02827_amd.sweep --config 4 --alpha 0.05 0.1 0.2 0.5 1.0 --K 1 5 10 50
+    python -m paper_2602_02827_amd.sweep --config 4 --alpha 1.0 --K 1 5 10 50 --interval-miss 8
     python -m paper_2602_02827_amd.sweep --config 2 --K 100 500 1000 --M 0 5 10
     python -m paper_2602_02827_amd.sweep --config 2 --nq 1            # single-query latency
     python -m paper_2602_02827_amd.sweep --config 2 --nq 1 --int8     # ... with int8 elimination rounds
@@ -12,7 +13,11 @@ colbandit_topk (events around `--reps` back-to-back asynchronous calls), coverag
 (unique revealed cells / (N*T), Sec. 3.1 Eq. (6)), Overlap@K against the exhaustive top-K, mean
 rounds and survivors entering the rescore.  `--gamma` / `--tau` add one line per setting of the
 paper's two non-adaptive baselines, Doc-Uniform and Ball-carving (appendix "Compared Methods"),
-with the same Overlap@K and their coverage (ceil(gamma T)/T, mean k/T).  The grid of alpha_ef x K follows the knob sweeps of
+with the same Overlap@K and their coverage (ceil(gamma T)/T, mean k/T).  `--interval-miss Q`
+traces the first Q queries of every Col-Bandit setting and counts how often the exhaustive score
+of a live document lies outside its decision interval [LCB, UCB] (Theorem 1 and the remark on its
+scope: at alpha_ef = 1 the intervals hold jointly with probability 1 - delta only up to the
+simplified radius; at alpha_ef < 1 misses are expected).  The grid of alpha_ef x K follows the knob sweeps of
 the paper's evaluation (Sec. 5, implementation appendix "Default parameter setting").
 """
 from __future__ import annotations
@@ -39,6 +44,9 @@ def main(argv=None):
                     help="Ball-carving cosine thresholds")
     ap.add_argument("--int8", action="store_true",
                     help="run the elimination rounds on int8 codes of the corpus (coded once, untimed)")
+    ap.add_argument("--interval-miss", type=int, default=0, metavar="Q",
+                    help="trace the first Q queries and count live documents whose exhaustive score "
+                         "leaves [LCB, UCB]")
     args = ap.parse_args(argv)
 
     import numpy as np
@@ -66,6 +74,33 @@ def main(argv=None):
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / args.reps
+
+    nmiss = min(args.interval_miss, nq)
+    S_traced = None
+    if nmiss > 0:       # exhaustive scores of the traced queries (the bounds are about these)
+        S_traced = B.colbandit_full_maxsim(w.Q[:nmiss].contiguous(), w.docs, w.offsets, K=0)["scores"].cpu().numpy()
+
+    def interval_misses(K, alpha, M):
+        """Theorem 1's event on the traced queries: per (round, live document), is the exhaustive
+        score inside [LCB, UCB]?  The bounds are fp32 on the device: 1e-4 of slack."""
+        r = B.colbandit_topk(w.Q, w.docs, w.offsets, K, alpha, w.delta, M, w.seed, B=args.B,
+                             workspace=ws, trace=True, trace_queries=list(range(nmiss)))
+        tr = r["trace"]
+        checks = misses = q_miss = below = 0
+        for q in range(nmiss):
+            any_miss = False
+            for rr in range(r["stats"][q]["rounds"]):
+                live = ~np.isnan(tr.lcb[rr, q])
+                lo = S_traced[q][live] < tr.lcb[rr, q][live] - 1e-4
+                hi = S_traced[q][live] > tr.ucb[rr, q][live] + 1e-4
+                checks += int(live.sum())
+                misses += int(lo.sum() + hi.sum())
+                below += int(lo.sum())
+                any_miss |= bool(lo.any() or hi.any())
+            q_miss += any_miss
+        return {"traced_queries": nmiss, "interval_checks": checks, "misses": misses,
+                "misses_score_below_lcb": below, "miss_rate": round(misses / max(1, checks), 6),
+                "queries_with_a_miss": q_miss, "delta": w.delta}
 
     for K in args.K:
         full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K, workspace=ws, want_scores=False)
@@ -117,16 +152,19 @@ def main(argv=None):
                 st = res["stats"]
                 overlap = float(np.mean([len(set(ids_full[q]) & set(ids[q])) / K for q in range(nq)]))
                 cov = sum(s["cells_unique"] for s in st) / (float(nq) * N * T)
+                extra = {"interval_miss": interval_misses(K, alpha, M)} if nmiss > 0 else {}
                 print(json.dumps({
                     "workload": w.name, "n_queries": nq, "N": N, "T": T, "d": d, "K": K,
                     "method": "colbandit", "alpha_ef": alpha,
                     "M": M, "B": args.B, "reveals": "int8" if args.int8 else w.dtype, "full_ms": round(ms_full, 3), "colbandit_ms": round(ms_cb, 3),
                     "speedup": round(ms_full / ms_cb, 2), "coverage": round(cov, 4),
+                    "computed_cells_over_all_cells": round(sum(s["cells_computed"] for s in st) / (float(nq) * N * T), 4),
                     "overlap_at_k": round(overlap, 4),
                     "mean_rounds": round(float(np.mean([s["rounds"] for s in st])), 2),
                     "mean_rescored": round(float(np.mean([s["survivors"][s["rounds"]] for s in st])), 1),
                     "ms_phases": {k[3:]: round(st[0][k], 3) for k in
                                   ("ms_first_reveal", "ms_later_reveals", "ms_select_prune", "ms_rescore_topk")},
+                    "corpus_pass_rounds": st[0]["corpus_pass_rounds"], **extra,
                 }), flush=True)
 
 

@@ -259,6 +259,12 @@ def _run_colbandit_case(B, oracle_mod, w, K, M, Bsz, alpha, delta=0.01, seed=0, 
         else:
             diverged += 1
     assert diverged <= max(1, int(0.15 * w.nq)), diverged
+    # what a gathered round 2 has to read: the pairs that entered it and their document tokens
+    if tr.count.shape[0] >= 3:
+        L = np.diff(w.offsets.cpu().numpy())
+        goes_on = [q for q in range(w.nq) if res["stats"][q]["rounds"] >= 1 and tr.count[1, q] > K + M]
+        assert res["stats"][0]["pairs_round2"] == sum(int(tr.count[1, q]) for q in goes_on)
+        assert res["stats"][0]["tokens_round2"] == sum(int(L[tr.alive[0, q]].sum()) for q in goes_on)
     return res, tr
 
 
@@ -307,7 +313,8 @@ def _same_run(r1, r2):
         np.testing.assert_array_equal(getattr(r1["trace"], f), getattr(r2["trace"], f))
     assert torch.equal(r1["topk_ids"], r2["topk_ids"]) and torch.equal(r1["topk_scores"], r2["topk_scores"])
     # which path computed a round's cells may differ between the runs; nothing else may
-    counts = lambda st: {k: v for k, v in st.items() if not k.startswith("ms_") and k != "corpus_pass_rounds"}
+    counts = lambda st: {k: v for k, v in st.items() if not k.startswith("ms_")
+                         and k not in ("corpus_pass_rounds", "cells_computed")}
     assert [counts(a) for a in r1["stats"]] == [counts(b) for b in r2["stats"]]
 
 
@@ -364,11 +371,34 @@ def test_device_side_choice_takes_the_corpus_pass_for_large_active_sets(B, S):
     torch.cuda.synchronize()
     assert torch.equal(res[0]["topk_ids"], res[2]["topk_ids"])
     assert torch.equal(res[0]["topk_scores"], res[2]["topk_scores"])
-    c = lambda st: {k: v for k, v in st.items() if not k.startswith("ms_") and k != "corpus_pass_rounds"}
+    c = lambda st: {k: v for k, v in st.items() if not k.startswith("ms_")
+                    and k not in ("corpus_pass_rounds", "cells_computed")}
     assert [c(a) for a in res[0]["stats"]] == [c(b) for b in res[2]["stats"]]
     assert 2 in res[0]["stats"][0]["corpus_pass_rounds"] and res[2]["stats"][0]["corpus_pass_rounds"] == []
     print("later reveals: auto %.3f ms, gather %.3f ms" %
           (res[0]["stats"][0]["ms_later_reveals"], res[2]["stats"][0]["ms_later_reveals"]))
+
+
+def test_cells_computed_counts_what_the_kernels_multiply(B, S):
+    """cells_computed against the path each round took: per-pair gathers without the cache
+    compute exactly the revealed cells; with the cache the first gathered round computes all T
+    cells of its documents and nothing afterwards; a corpus pass computes the batch for all N."""
+    rng = np.random.default_rng(12)
+    w = _custom(S, rng.integers(1, 90, 3000).tolist(), 4, 32, 128, "bf16", 19)
+    N, T, Bsz = w.N, w.T, 4
+    plain = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.5, 0.01, 5, 4, no_cell_cache=True, later_rounds=2)
+    cached = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.5, 0.01, 5, 4, later_rounds=2)
+    passes = B.colbandit_topk(w.Q, w.docs, w.offsets, 5, 0.5, 0.01, 5, 4, later_rounds=1, no_cell_cache=True)
+    torch.cuda.synchronize()
+    assert max(s["rounds"] for s in plain["stats"]) >= 3
+    for sp, sc, sd in zip(plain["stats"], cached["stats"], passes["stats"]):
+        assert sp["survivors"] == sc["survivors"] == sd["survivors"]
+        surv, R = sp["survivors"], sp["rounds"]
+        assert sp["cells_computed"] == sp["cells_elim"] + sp["cells_rescore"]
+        want = Bsz * N + (T * surv[1] if R >= 2 else T * surv[R])      # round 1, then one visit
+        assert sc["cells_computed"] == want
+        assert sd["cells_computed"] == Bsz * N * R + T * surv[R]       # every round a pass, then the rescore
+        assert sd["corpus_pass_rounds"] == list(range(2, 2 + len(sd["corpus_pass_rounds"])))
 
 
 def test_active_sets_larger_than_the_cell_cache(B, S, oracle_mod):
