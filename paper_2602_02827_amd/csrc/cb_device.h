@@ -461,10 +461,19 @@ __device__ __forceinline__ void merge_stats(float& S, float& M2, int n_prev, flo
     S += sb;
 }
 
+// NaN test on the bit pattern: device code is compiled under the assumption that floating-point
+// comparisons never see a NaN, so a comparison cannot be trusted to detect one.
+__device__ __forceinline__ bool is_nan_bits(float x) {
+    return (__float_as_uint(x) & 0x7fffffffu) > 0x7f800000u;
+}
+
 // Hybrid decision interval (paper Eq. (8)) from a document's revealed sum S and centred
 // squares M2 after n cells: hard bounds S + (T-n)[a,b], estimator T*S/n, radius
 // kappa*sigma_hat with sigma_hat^2 = M2/(n-1) (Appendix A).  n <= 1: hard bounds only;
 // n == T: the interval is the exact sum.
+// Inputs outside the contract (a document without tokens has cells -inf and M2 = NaN; NaN
+// embeddings give NaN cells) yield the interval [-inf, -inf]: such a document is dropped as soon
+// as K others exist and never disturbs the threshold of the rest.
 __device__ __forceinline__ void interval(float S, float M2, int n, int T, float kappa, float a,
                                          float b, float& lcb, float& ucb) {
     const float rest = (float)(T - n);
@@ -472,26 +481,30 @@ __device__ __forceinline__ void interval(float S, float M2, int n, int T, float 
     if (n <= 1) {
         lcb = lb;
         ucb = ub;
-        return;
-    }
-    if (n >= T) {
+    } else if (n >= T) {
         lcb = S;
         ucb = S;
-        return;
+    } else {
+        const float shat = (float)T * (S / (float)n);
+        const float sigma = sqrtf(fmaxf(M2, 0.f) / (float)(n - 1));
+        const float r = kappa * sigma;
+        lcb = fmaxf(lb, shat - r);
+        ucb = fminf(ub, shat + r);
     }
-    const float shat = (float)T * (S / (float)n);
-    const float sigma = sqrtf(fmaxf(M2, 0.f) / (float)(n - 1));
-    const float r = kappa * sigma;
-    lcb = fmaxf(lb, shat - r);
-    ucb = fminf(ub, shat + r);
+    if (is_nan_bits(S) || is_nan_bits(M2) || is_nan_bits(lcb) || is_nan_bits(ucb)) {
+        lcb = -__builtin_inff();
+        ucb = -__builtin_inff();
+    }
 }
 
-// Order-preserving map float -> uint32 (larger float, larger key).
+// Order-preserving map float -> uint32 (larger float, larger key); NaN maps below everything.
 __device__ __forceinline__ uint32_t float_key(float f) {
+    if (is_nan_bits(f)) return 0u;
     uint32_t u = __float_as_uint(f + 0.0f);   // -0 and +0 share a key
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 __device__ __forceinline__ float key_float(uint32_t k) {
+    if (k < 0x007fffffu) return -__builtin_inff();      // below the key of -inf: NaN's key
     uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
     return __uint_as_float(u);
 }

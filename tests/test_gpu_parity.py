@@ -134,6 +134,48 @@ def test_documents_without_tokens_get_minus_infinity_and_disturb_nothing(B, S, o
         assert np.all(np.isneginf(got[q][[i for i, n in enumerate(lengths) if n == 0]]))
 
 
+def test_nan_rows_and_token_less_documents_do_not_damage_other_documents(B, S, oracle_mod):
+    """Inputs outside the contract: one document whose embeddings are NaN, one without tokens.
+    Their own scores are meaningless, but they must neither enter a top-K nor wipe out a query's
+    threshold: every other document keeps its exact score, the exhaustive top-K is the ordered
+    head of the valid scores, and Col-Bandit returns K valid documents with those scores."""
+    rng = np.random.default_rng(61)
+    lengths = rng.integers(20, 90, 1200).tolist()
+    p_nan, r_empty = 333, 700
+    lengths[r_empty] = 0
+    w = _custom(S, lengths, 4, 32, 128, "bf16", 67)
+    off = w.offsets.cpu().numpy()
+    w.docs[int(off[p_nan]):int(off[p_nan + 1])] = float("nan")
+    K = 6
+    full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K)
+    res = B.colbandit_topk(w.Q, w.docs, w.offsets, K, 0.3, 0.01, 5, 8, trace=True)
+    plain = B.colbandit_topk(w.Q, w.docs, w.offsets, K, 0.3, 0.01, 5, 8)       # untraced code paths
+    gathered = B.colbandit_topk(w.Q, w.docs, w.offsets, K, 0.3, 0.01, 5, 8, force_gather=True,
+                                no_cell_cache=True)
+    torch.cuda.synchronize()
+    for other in (plain, gathered):
+        assert torch.equal(other["topk_ids"], res["topk_ids"])
+        assert torch.equal(other["topk_scores"], res["topk_scores"])
+    sc = full["scores"].cpu().numpy()
+    bad = np.array([p_nan, r_empty])
+    good = np.setdiff1d(np.arange(w.N), bad)
+    # the hardware maximum drops a NaN operand, so the NaN document scores -inf (NaN would do too)
+    assert np.all(np.isnan(sc[:, p_nan]) | np.isneginf(sc[:, p_nan])) and np.all(np.isneginf(sc[:, r_empty]))
+    E, offg = w.host_docs(good.tolist())
+    for q in range(w.nq):
+        want = oracle_mod.row_sums(oracle_mod.maxsim_cells(w.host_queries()[q], E, offg))
+        np.testing.assert_allclose(sc[q][good], want, rtol=TOL["bf16"], atol=1e-4)
+        order = good[np.lexsort((good, -sc[q][good]))][:K]
+        np.testing.assert_array_equal(full["topk_ids"][q].cpu().numpy(), order)
+        ids = res["topk_ids"][q].cpu().numpy()
+        assert len(set(ids.tolist())) == K and not (set(ids.tolist()) & set(bad.tolist())) and ids.min() >= 0
+        np.testing.assert_array_equal(res["topk_scores"][q].cpu().numpy(), sc[q][ids])
+        st = res["stats"][q]
+        assert st["rounds"] >= 1 and st["survivors"][st["rounds"]] >= K
+        assert not res["trace"].alive[0, q][bad].any()          # both dropped in the first round
+        assert not np.isnan(res["trace"].tau[0, q])
+
+
 def test_topk_ties_resolve_to_lower_index(B, S):
     # documents 10.. are exact copies of documents 0..9 -> exact score ties
     base = _custom(S, [20] * 10, 2, 32, 128, "bf16", 3)
