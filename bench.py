@@ -36,11 +36,17 @@ CALIBRATION_COPY_BYTES = 1 << 30
 
 
 def kernel_source_hash():
+    """Hash of the kernel sources with comments and white space removed (a comment may change
+    without making a counter reading stale; code may not)."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for f in KERNEL_SOURCES:
-        with open(os.path.join(ROOT, "paper_2602_02827_amd", "csrc", f), "rb") as fh:
-            h.update(fh.read())
+        with open(os.path.join(ROOT, "paper_2602_02827_amd", "csrc", f), "r") as fh:
+            text = fh.read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", "", text)
+        h.update(re.sub(r"\s+", "", text).encode())
     return h.hexdigest()[:16]
 
 
@@ -54,7 +60,7 @@ def measured_traffic(workload_key):
     have = kernel_source_hash()
     for line in open(TRAFFIC_FILE):
         f = line.split()
-        if len(f) < 3 or f[0] != "record":
+        if len(f) < 3 or f[0] != "record" or not all("=" in x for x in f[2:]):
             continue
         kv = dict(x.split("=", 1) for x in f[2:])
         if kv.get("workload") != workload_key or kv.get("sources") != have:

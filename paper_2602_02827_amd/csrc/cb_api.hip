@@ -43,8 +43,12 @@ Layout make_layout(int nq, int T, int d, int64_t N, int64_t total_tokens) {
     L.stat2 = take(8 * qn);
     L.pairs = take(8 * 2 * (size_t)(COLBANDIT_MAX_ROUNDS + 4));
     L.seg_cnt = take(4 * (size_t)nq * 64);
-    L.rescored = take(4 * qn);
-    L.scores = take(4 * qn);
+    // Two arrays share storage with arrays that are dead while they live: the exhaustive
+    // path's score rows (no call uses them together with the running statistics) lie over
+    // `stat`, and the rescored survivors (written after the last round) over `stat2`, which
+    // only a round's corpus pass and the prune right after it use.
+    L.scores = L.stat;
+    L.rescored = L.stat2;
     L.cnt_hist = take(4 * (size_t)(COLBANDIT_MAX_ROUNDS + 2) * nq);
     L.tau_hist = take(4 * (size_t)(COLBANDIT_MAX_ROUNDS + 2) * nq);
     L.pi = take(4 * (size_t)nq * T);

@@ -183,53 +183,30 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
     }
 
     const int stride = gridDim.x * 4;
-    // entry k of the list -> document id and its token range (clamped into the corpus)
-    auto pair_of = [&](int k, int& id, int64_t& o0, int64_t& o1) {
-        id = list ? list[k] : k;
+    for (int k = first; k < count; k += stride) {
+        int id = list ? list[k] : k;
         if (slot_ids) id = slot_ids[id];
-        o0 = A.off[id];
-        o1 = A.off[id + 1];
+        int64_t o0 = A.off[id], o1 = A.off[id + 1];
         o0 = o0 < 0 ? 0 : (o0 > A.total ? A.total : o0);
         o1 = o1 < o0 ? o0 : (o1 > A.total ? A.total : o1);
-    };
-    // one block of 16 token rows starting at r0 (rows past the document's end repeat its last token)
-    auto load_rows = [&](F& a, int64_t r0, int64_t o1) {
-        int64_t row = r0 + col;
-        row = row < o1 ? row : o1 - 1;
-        a.load((const char*)A.docs + (size_t)row * row_bytes, kg);
-    };
-    int id;
-    int64_t o0, o1;
-    pair_of(first, id, o0, o1);
-    for (int k = first; k < count; k += stride) {
-        // The next pair's list entry and offsets are requested now and used after this pair's
-        // blocks, and two token blocks are kept in flight: a gathered document is a chain of
-        // dependent memory latencies (entry -> offsets -> tokens), which this hides.
-        int id_n = id;
-        int64_t o0_n = o0, o1_n = o1;
-        if (k + stride < count) pair_of(k + stride, id_n, o0_n, o1_n);
 
         V h[TQ];
 #pragma unroll
         for (int tt = 0; tt < TQ; ++tt) h[tt] = lowest_val<V>();
 
-        auto fold_block = [&](const F& a) {
+        // One block of 16 rows in flight per wavefront: the many wavefronts a CU holds already
+        // fill the memory system (a deeper per-wavefront pipeline - two blocks and the next
+        // pair's offsets in flight - was measured and changed neither the time nor the traffic).
+        for (int64_t r0 = o0; r0 < o1; r0 += 16) {
+            int64_t row = r0 + col;
+            row = row < o1 ? row : o1 - 1;
+            F a;
+            a.load((const char*)A.docs + (size_t)row * row_bytes, kg);
 #pragma unroll
             for (int tt = 0; tt < TQ; ++tt) {
                 typename F::acc_t acc = {0, 0, 0, 0};
                 F::mma(acc, a, bq[tt]);
                 h[tt] = fold_max(h[tt], acc);
-            }
-        };
-        F a0, a1;
-        if (o0 < o1) load_rows(a0, o0, o1);
-        if (o0 + 16 < o1) load_rows(a1, o0 + 16, o1);
-        for (int64_t r0 = o0; r0 < o1; r0 += 32) {
-            fold_block(a0);
-            if (r0 + 32 < o1) load_rows(a0, r0 + 32, o1);
-            if (r0 + 16 < o1) {
-                fold_block(a1);
-                if (r0 + 48 < o1) load_rows(a1, r0 + 48, o1);
             }
         }
 
@@ -298,9 +275,6 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A) {
                 }
             }
         }
-        id = id_n;
-        o0 = o0_n;
-        o1 = o1_n;
     }
 }
 
