@@ -165,9 +165,9 @@ size_t colbandit_workspace_bytes(int n_queries, int T, int d, int64_t N,
                                  int64_t total_tokens, int K, int M);
 
 /*
- * int8 codes for the coarse elimination pass (implementation appendix, "Cache-separated
- * quantized layout": clip to the 99.9th percentile of the absolute values, then linear
- * quantisation to int8).  The input is n_segments consecutive matrices of
+ * int8 codes for the coarse elimination pass (implementation appendix, paragraph on the
+ * quantized layout: magnitudes are clipped at a high percentile, 999 per mille, and the
+ * clipped range is coded linearly in 8 bits).  The input is n_segments consecutive matrices of
  * rows_per_segment x d values; each segment gets its own clip value: the nearest-rank
  * percentile of |x|, i.e. the element of rank ceil(n * permille / 1000) of the ascending
  * order of the segment's n = rows_per_segment * d absolute values (exact, no

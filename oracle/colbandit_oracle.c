@@ -493,9 +493,9 @@ int oracle_colbandit_coarse(const double *H_coarse, const double *H_exact, int64
 }
 
 /* ------------------------------------------------------------------ */
-/* int8 coarse pass (implementation appendix, "Cache-separated          */
-/* quantized layout": clip to the 99.9th percentile of the absolute     */
-/* values, then linear quantisation to int8)                            */
+/* int8 coarse pass (implementation appendix, paragraph on the         */
+/* quantized layout: magnitudes clipped at the 999th permille, the     */
+/* clipped range coded linearly in 8 bits)                             */
 /* ------------------------------------------------------------------ */
 
 static int cmp_float_asc(const void *pa, const void *pb)

@@ -1,6 +1,6 @@
-// int8 codes for the coarse elimination pass (paper, implementation appendix,
-// "Cache-separated quantized layout": clip to the 99.9th percentile of the absolute values,
-// then linear quantisation to int8).
+// int8 codes for the coarse elimination pass (paper, implementation appendix, paragraph on the
+// quantized layout: magnitudes are clipped at the 999th permille and the clipped range is coded
+// linearly in 8 bits).
 //
 // Reading of the paper fixed here: the percentile is the nearest-rank one -- the element of
 // rank ceil(n * permille / 1000) of the ascending order of |x| over one segment (the whole

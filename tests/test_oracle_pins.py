@@ -478,8 +478,8 @@ def test_pac_corner_over_all_permutations(oracle_mod):
 
 
 # ------------------------------------------------------------------ int8 coarse pass
-# (implementation appendix, "Cache-separated quantized layout": clip at the 99.9th percentile of
-# the absolute values, linear int8 codes, decisions on the coarse cells, exact rescore)
+# (implementation appendix, paragraph on the quantized layout: magnitudes clipped at the 999th
+# permille, linear 8-bit codes, decisions on the coarse cells, exact rescore)
 
 def test_abs_percentile_is_the_nearest_rank_statistic(oracle_mod):
     rng = np.random.default_rng(5)
