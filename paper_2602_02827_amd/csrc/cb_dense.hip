@@ -26,6 +26,9 @@
 namespace cb {
 
 constexpr int DENSE_THREADS = 256;
+#ifndef CB_TWO_IN_FLIGHT
+#define CB_TWO_IN_FLIGHT 0
+#endif
 // Ring geometry: four stages.  Kernels with few column tiles per wavefront (small query
 // batches: bound by memory, little register use) take 32-row stages, so that four workgroups fit
 // a CU instead of two and more wavefronts hide the latencies; the others take 64-row stages.
@@ -73,6 +76,7 @@ void k_dense(DenseArgs A) {
     constexpr bool CODES = !__is_same(V, float);
     constexpr int ROWB = D * F::ELEM_BYTES;   // bytes per token row
     constexpr int NCH = ROWB / 16;         // 16-byte pieces per row
+    constexpr bool TWO_IN_FLIGHT = CB_TWO_IN_FLIGHT;
     // Swizzle key of a ring row: rows whose 16-byte pieces would fall on the same banks
     // (row stride ROWB against the 256-byte bank window) get different keys.
     constexpr int KEY_SHIFT = NCH >= 16 ? 0 : (NCH == 8 ? 1 : 2);
@@ -166,8 +170,6 @@ void k_dense(DenseArgs A) {
             }
         }
     };
-    // the copies of a stage must have landed before the barrier that publishes it
-    auto stage_wait = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */ };
 
     // ---- document walk state (identical in all four wavefronts)
     int ibase = i0;
@@ -272,26 +274,50 @@ void k_dense(DenseArgs A) {
         for (int tt = 0; tt < NT; ++tt) h[tt] = lowest_val<V>();
     };
 
-    // one block of 16 tokens against all NT column tiles
-    // ---- stage bookkeeping.  `published` stages are visible to every wavefront, stage
-    // `published` (if any) is in flight.  All four wavefronts walk the same documents and
-    // blocks, so they call stage_advance at the same points and its barrier matches up.
-    // Slot safety: when stage P starts to load into slot P & 3, no block can still need a
-    // row of stage P - 4 (the reader is at most 15 rows behind stage P - 2).
+    // ---- stage bookkeeping.  The reader walks the chunk stage by stage; when it enters stage st
+    // the stages up to st+1 are visible to every wavefront (the first block of st+1 is read as
+    // the "next block" while the last block of st is multiplied) and the following stage (or
+    // two) is in flight.  All four wavefronts walk the same blocks, so they reach stage_enter at
+    // the same points and its barrier matches up.
+    // Slot safety: a stage is requested into the slot of a stage at least two behind the
+    // reader, which no wavefront reads any more once all have passed the barrier.
     const int nst = (ntok + STAGE_ROWS - 1) / STAGE_ROWS;
+    const int nfull = ntok / STAGE_ROWS;            // stages with all their rows
+    // wait until the copies of every stage but the most recently requested one have landed.  A
+    // complete stage is LOADS_PER_WAVE copies per wavefront and loads retire in order, so "at
+    // most LOADS_PER_WAVE outstanding" says exactly that; an incomplete (last) stage may have
+    // issued fewer, then everything is awaited.
+    auto wait_older = [&](int latest) {
+        constexpr int WAIT_KEEP = 0x0F70 | (LOADS_PER_WAVE & 0xF) | ((LOADS_PER_WAVE >> 4) << 14);
+        if (TWO_IN_FLIGHT && latest < nfull) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
+        else __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    };
+    // Workgroup barrier without a memory fence: the copies a wavefront is responsible for have
+    // been awaited explicitly just before, every ring read of the slot that is about to be
+    // overwritten has been consumed by its MFMAs, and younger copies may stay in flight across
+    // the barrier.  The empty asm statements keep the compiler from moving ring accesses across.
+    auto ring_barrier = [&]() {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
     stage_fetch(0);
     if (nst > 1) stage_fetch(1);
-    stage_wait();
-    __syncthreads();
-    int published = nst < 2 ? nst : 2;
-    if (published < nst) stage_fetch(published);
-    int avail = published * STAGE_ROWS < ntok ? published * STAGE_ROWS : ntok;
-    auto stage_advance = [&]() {
-        stage_wait();
-        __syncthreads();
-        ++published;
-        if (published < nst) stage_fetch(published);
-        avail = published * STAGE_ROWS < ntok ? published * STAGE_ROWS : ntok;
+    if (TWO_IN_FLIGHT && nst > 2) stage_fetch(2);
+    wait_older(TWO_IN_FLIGHT && nst > 2 ? 2 : nst);
+    ring_barrier();
+    if (TWO_IN_FLIGHT) {
+        if (nst > 3) stage_fetch(3);
+    } else if (nst > 2) {
+        stage_fetch(2);
+    }
+    // the reader enters stage st >= 1: publish stage st+1, request the next one
+    auto stage_enter = [&](int st) {
+        if (st + 1 >= nst) return;                  // everything is visible already
+        wait_older(st + 2 < nst ? st + 2 : nst);
+        ring_barrier();
+        const int req = TWO_IN_FLIGHT ? st + 3 : st + 2;
+        if (req < nst) stage_fetch(req);
     };
 
     // ---- block stream.  The chunk's tokens are one stream cut into aligned blocks of 16 rows,
@@ -308,17 +334,21 @@ void k_dense(DenseArgs A) {
 #pragma unroll
     for (int ks = 0; ks < F::KS; ++ks)
         blk_off[ks] = (unsigned)(col * ROWB + (((ks * 4 + kg) ^ ((col >> KEY_SHIFT) & (NCH - 1))) * 16));
+    // a complete block (bs + 16 <= ntok) of a visible stage
+    auto load_aligned = [&](F& a, int bs) {
+        using piece_t = __remove_reference_t(decltype(a.v[0]));
+        const char* rp = ring + (bs & (RING_ROWS - 1)) * ROWB;       // uniform
+#pragma unroll
+        for (int ks = 0; ks < F::KS; ++ks) a.v[ks] = *(const piece_t*)(rp + blk_off[ks]);
+    };
+    // any block of a visible stage; the chunk's last block repeats the last token
     auto load_block = [&](F& a, int bs) {
         using piece_t = __remove_reference_t(decltype(a.v[0]));
-        const int end = bs + 16 < ntok ? bs + 16 : ntok;
-        while (end > avail) stage_advance();    // end <= ntok, so this stops at the last stage
         if (bs + 16 <= ntok) {
-            const char* rp = ring + (bs & (RING_ROWS - 1)) * ROWB;       // uniform
-#pragma unroll
-            for (int ks = 0; ks < F::KS; ++ks) a.v[ks] = *(const piece_t*)(rp + blk_off[ks]);
+            load_aligned(a, bs);
             return;
         }
-        int row = bs + col;                      // the chunk's last block: repeat the last token
+        int row = bs + col;
         row = row < ntok ? row : ntok - 1;
         const char* rp = ring + (row & (RING_ROWS - 1)) * ROWB;
         const int sw = (row >> KEY_SHIFT) & (NCH - 1);
@@ -365,20 +395,50 @@ void k_dense(DenseArgs A) {
         }
     };
 
-    // ---- consumer: the MFMAs of block k overlap the operand reads of block k+1
+    // ---- consumer: the MFMAs of block k overlap the operand reads of block k+1.  Runs of
+    // blocks that lie inside one document and inside a stage whose successor block is complete
+    // too go through a loop that holds nothing but the operand reads and the MFMAs of two
+    // blocks; a block in which a document ends, and every block of the chunk's last one or two
+    // stages, takes the general path.  a0 always holds the block at bs.  Kernels with fewer than
+    // eight column tiles per wavefront are bound by memory, not by the matrix pipes, and run at
+    // a higher occupancy with fewer registers: they keep to the general path.
+    constexpr bool TIGHT_RUNS = NT >= 8;
     F a0, a1;
     int bs = 0;
     load_block(a0, 0);
-    while (bs < ntok) {
-        if (bs + 16 < ntok) load_block(a1, bs + 16);
-        __builtin_amdgcn_sched_barrier(0);      // keep the reads of the next block up here
-        process(a0, bs);
-        bs += 16;
-        if (bs >= ntok) break;
-        if (bs + 16 < ntok) load_block(a0, bs + 16);
-        __builtin_amdgcn_sched_barrier(0);
-        process(a1, bs);
-        bs += 16;
+    for (int st = 0; st < nst; ++st) {
+        if (st > 0) stage_enter(st);
+        const int s_end = (st + 1) * STAGE_ROWS < ntok ? (st + 1) * STAGE_ROWS : ntok;
+        const bool whole = (st + 1) * STAGE_ROWS + 16 <= ntok;
+        while (bs < s_end) {
+            if (TIGHT_RUNS && whole) {
+                // blocks from bs on that end before the current document does, within this stage
+                int run = doc < i1 ? (dend - bs - 1) >> 4 : STAGE_ROWS / 16;
+                const int left = (s_end - bs) >> 4;
+                run = run < 0 ? 0 : (run > left ? left : run);
+#pragma unroll 1
+                for (; run >= 2; run -= 2) {
+                    load_aligned(a1, bs + 16);
+                    block_mma<NT>(a0, bq, h);
+                    load_aligned(a0, bs + 32);
+                    block_mma<NT>(a1, bq, h);
+                    bs += 32;
+                }
+                if (run == 1) {
+                    load_aligned(a1, bs + 16);
+                    __builtin_amdgcn_sched_barrier(0);
+                    block_mma<NT>(a0, bq, h);
+                    a0 = a1;
+                    bs += 16;
+                }
+                if (bs >= s_end) break;
+            }
+            if (bs + 16 < ntok) load_block(a1, bs + 16);
+            __builtin_amdgcn_sched_barrier(0);      // keep the reads of the next block up here
+            process(a0, bs);
+            a0 = a1;
+            bs += 16;
+        }
     }
     while (doc < i1) finalize(doc++);           // documents without tokens at the chunk's end
 }
