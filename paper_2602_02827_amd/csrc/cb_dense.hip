@@ -91,7 +91,11 @@ void k_dense(DenseArgs A) {
     const int b = blockIdx.x;
     const int xcd = b & 7, slot = b >> 3;
     const int group = slot % A.n_groups;
-    const int chunk = (slot / A.n_groups) * 8 + xcd;
+    // Eight consecutive chunks go to the eight XCDs, rotated from one eight to the next by a
+    // mix of its number: documents much longer than a chunk leave all but every 2^k-th chunk
+    // empty, and a fixed chunk -> XCD map would then put all the work on a few XCDs.
+    const int k8 = slot / A.n_groups;
+    const int chunk = k8 * 8 + ((xcd + k8 + (k8 >> 3) + (k8 >> 6) + (k8 >> 9)) & 7);
     if (chunk >= A.n_chunks) return;
     if constexpr (REVEAL) {
         if (A.pairs_r && !dense_round(A.pairs_r, A.dense_thr)) return;
@@ -395,50 +399,71 @@ void k_dense(DenseArgs A) {
         }
     };
 
-    // ---- consumer: the MFMAs of block k overlap the operand reads of block k+1.  Runs of
-    // blocks that lie inside one document and inside a stage whose successor block is complete
-    // too go through a loop that holds nothing but the operand reads and the MFMAs of two
-    // blocks; a block in which a document ends, and every block of the chunk's last one or two
-    // stages, takes the general path.  a0 always holds the block at bs.  Kernels with fewer than
-    // eight column tiles per wavefront are bound by memory, not by the matrix pipes, and run at
-    // a higher occupancy with fewer registers: they keep to the general path.
+    // ---- consumer: the MFMAs of block k overlap the operand reads of block k+1.  a0 always
+    // holds the block at bs; the stage that begins at bs (if one does) is entered just before
+    // block bs is multiplied.  Runs of blocks that lie inside one document go through a loop
+    // that holds nothing but the operand reads and the MFMAs of two blocks (and, every fourth
+    // block, the stage entry); it covers the rows below tight_end, where every block has a
+    // complete successor and every stage entered requests a complete stage.  A block in which a
+    // document ends, and the chunk's last stages, take the general path.  Kernels with fewer
+    // than eight column tiles per wavefront are bound by memory, not by the matrix pipes, and run
+    // at a higher occupancy with fewer registers: they keep to the general path.
     constexpr bool TIGHT_RUNS = NT >= 8;
+    const int tight_end = TIGHT_RUNS ? (nfull - 2) * STAGE_ROWS : 0;
+    auto stage_enter_full = [&](int bs) {        // bs < tight_end is a stage boundary
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+        ring_barrier();
+#pragma unroll
+        for (int i = 0; i < LOADS_PER_WAVE; ++i) {
+            const int r0 = bs + 2 * STAGE_ROWS + i * 4 * ROWS_PER_LOAD;               // uniform
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(src + (size_t)r0 * ROWB + fetch_off),
+                (__attribute__((address_space(3))) void*)(ring + ((r0 + wave * ROWS_PER_LOAD) & (RING_ROWS - 1)) * ROWB),
+                16, 0, 0);
+        }
+    };
+    auto at_boundary = [&](int bs) { return (bs & (STAGE_ROWS - 1)) == 0 && bs > 0; };
     F a0, a1;
     int bs = 0;
     load_block(a0, 0);
-    for (int st = 0; st < nst; ++st) {
-        if (st > 0) stage_enter(st);
-        const int s_end = (st + 1) * STAGE_ROWS < ntok ? (st + 1) * STAGE_ROWS : ntok;
-        const bool whole = (st + 1) * STAGE_ROWS + 16 <= ntok;
-        while (bs < s_end) {
-            if (TIGHT_RUNS && whole) {
-                // blocks from bs on that end before the current document does, within this stage
-                int run = doc < i1 ? (dend - bs - 1) >> 4 : STAGE_ROWS / 16;
-                const int left = (s_end - bs) >> 4;
-                run = run < 0 ? 0 : (run > left ? left : run);
-#pragma unroll 1
-                for (; run >= 2; run -= 2) {
-                    load_aligned(a1, bs + 16);
-                    block_mma<NT>(a0, bq, h);
-                    load_aligned(a0, bs + 32);
-                    block_mma<NT>(a1, bq, h);
-                    bs += 32;
-                }
-                if (run == 1) {
-                    load_aligned(a1, bs + 16);
-                    __builtin_amdgcn_sched_barrier(0);
-                    block_mma<NT>(a0, bq, h);
-                    a0 = a1;
-                    bs += 16;
-                }
-                if (bs >= s_end) break;
+    while (bs < ntok) {
+        if (TIGHT_RUNS && !TWO_IN_FLIGHT && bs < tight_end) {
+            // blocks from bs on that end before the current document does
+            int run = doc < i1 ? (dend - bs - 1) >> 4 : RING_ROWS;
+            const int left = (tight_end - bs) >> 4;
+            run = run < 0 ? 0 : (run > left ? left : run);
+            if (run >= 1 && (bs & 16)) {        // to an even block: pairs never straddle a stage
+                load_aligned(a1, bs + 16);
+                __builtin_amdgcn_sched_barrier(0);
+                block_mma<NT>(a0, bq, h);
+                a0 = a1;
+                bs += 16;
+                --run;
             }
-            if (bs + 16 < ntok) load_block(a1, bs + 16);
-            __builtin_amdgcn_sched_barrier(0);      // keep the reads of the next block up here
-            process(a0, bs);
-            a0 = a1;
-            bs += 16;
+#pragma unroll 1
+            for (; run >= 2; run -= 2) {
+                if (at_boundary(bs)) stage_enter_full(bs);
+                load_aligned(a1, bs + 16);
+                block_mma<NT>(a0, bq, h);
+                load_aligned(a0, bs + 32);
+                block_mma<NT>(a1, bq, h);
+                bs += 32;
+            }
+            if (run == 1) {
+                if (at_boundary(bs)) stage_enter_full(bs);
+                load_aligned(a1, bs + 16);
+                __builtin_amdgcn_sched_barrier(0);
+                block_mma<NT>(a0, bq, h);
+                a0 = a1;
+                bs += 16;
+            }
         }
+        if (at_boundary(bs)) stage_enter(bs / STAGE_ROWS);
+        if (bs + 16 < ntok) load_block(a1, bs + 16);
+        __builtin_amdgcn_sched_barrier(0);      // keep the reads of the next block up here
+        process(a0, bs);
+        a0 = a1;
+        bs += 16;
     }
     while (doc < i1) finalize(doc++);           // documents without tokens at the chunk's end
 }
