@@ -652,6 +652,35 @@ def test_doc_uniform_budget_is_the_exact_ceiling_on_the_papers_sweep(oracle_mod)
             oracle_mod.cells_per_doc(bad, 32)
 
 
+def test_doc_uniform_subset_is_floyds_sampling_on_the_published_stream(oracle_mod):
+    """The stated reading of "uniformly, without replacement" (Doc-Uniform paragraph of the
+    appendix "Compared Methods"), written out with Python integers: a SplitMix64 stream per
+    (query, document) (the stream itself is pinned to its published vector), Floyd's subset
+    sampling with the index floor(z (j+1) / 2^64).  A change of the stream constants, of the
+    index map (a modulo instead of the scaled product), of the order of the draws or of the
+    collision rule fails it; it does not depend on the stored golden rows."""
+    golden, doc_mult, mod = 0x9E3779B97F4A7C15, 0xD1B54A32D192ED03, 2 ** 64
+    rng = np.random.default_rng(5)
+    cases = [(7, 3, 0, 32, 4), (0, 0, 0, 1, 1), (1, 0, 5, 64, 63), (2 ** 64 - 1, 127, 10 ** 9, 24, 7)]
+    cases += [(int(rng.integers(0, 2 ** 62)), int(rng.integers(0, 500)), int(rng.integers(0, 10 ** 7)),
+               int(T), int(rng.integers(0, T + 1))) for T in rng.integers(1, 65, 60)]
+    collisions = 0
+    for seed, q, i, T, m in cases:
+        key = oracle_mod.splitmix64_stream((seed + (q + 1) * golden) % mod, 1)[0]
+        draws = oracle_mod.splitmix64_stream((int(key) + (i + 1) * doc_mult) % mod, max(m, 1))
+        chosen = set()
+        for z, j in zip(draws, range(T - m, T)):
+            t = (int(z) * (j + 1)) >> 64
+            assert 0 <= t <= j
+            if t in chosen:
+                collisions += 1
+                t = j
+            chosen.add(t)
+        want = sum(1 << t for t in chosen)
+        assert oracle_mod.uniform_subset(seed, q, i, T, m) == want, (seed, q, i, T, m)
+    assert collisions > 0                      # the collision rule was exercised
+
+
 def test_doc_uniform_generator_is_frozen(oracle_mod):
     """The subset generator is this build's own definition; tests/golden/uniform_subsets.txt
     (written by make_uniform_subsets.py from the oracle) freezes it, so that a change of the
