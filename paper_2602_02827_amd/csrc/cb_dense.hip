@@ -77,6 +77,13 @@ void k_dense(DenseArgs A) {
     constexpr int ROWB = D * F::ELEM_BYTES;   // bytes per token row
     constexpr int NCH = ROWB / 16;         // 16-byte pieces per row
     constexpr bool TWO_IN_FLIGHT = CB_TWO_IN_FLIGHT;
+#ifndef CB_REVEAL_NT
+#define CB_REVEAL_NT 1
+#endif
+    // Cache policy of the token copies.  The reveal pass normally has one column group: a token
+    // row is read once and should not push the lines of the (sum, M2) array, which fill up over
+    // several documents, out of L2; its copies carry the non-temporal hint (bit 1).
+    constexpr int LOAD_POLICY = (REVEAL && CB_REVEAL_NT) ? 2 : 0;
     // Swizzle key of a ring row: rows whose 16-byte pieces would fall on the same banks
     // (row stride ROWB against the 256-byte bank window) get different keys.
     constexpr int KEY_SHIFT = NCH >= 16 ? 0 : (NCH == 8 ? 1 : 2);
@@ -155,7 +162,7 @@ void k_dense(DenseArgs A) {
                 __builtin_amdgcn_global_load_lds(
                     (const __attribute__((address_space(1))) void*)(src + (size_t)r0 * ROWB + fetch_off),
                     (__attribute__((address_space(3))) void*)(ring + ((r0 + wave * ROWS_PER_LOAD) & (RING_ROWS - 1)) * ROWB),
-                    16, 0, 0);
+                    16, 0, LOAD_POLICY);
             }
             return;
         }
@@ -170,7 +177,7 @@ void k_dense(DenseArgs A) {
                 __builtin_amdgcn_global_load_lds(
                     (const __attribute__((address_space(1))) void*)(src + (size_t)grow * ROWB + c * 16),
                     (__attribute__((address_space(3))) void*)(ring + (rbase & (RING_ROWS - 1)) * ROWB),
-                    16, 0, 0);
+                    16, 0, LOAD_POLICY);
             }
         }
     };
@@ -419,7 +426,7 @@ void k_dense(DenseArgs A) {
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void*)(src + (size_t)r0 * ROWB + fetch_off),
                 (__attribute__((address_space(3))) void*)(ring + ((r0 + wave * ROWS_PER_LOAD) & (RING_ROWS - 1)) * ROWB),
-                16, 0, 0);
+                16, 0, LOAD_POLICY);
         }
     };
     auto at_boundary = [&](int bs) { return (bs & (STAGE_ROWS - 1)) == 0 && bs > 0; };
