@@ -7,6 +7,7 @@
     python -m paper_2602_02827_amd.sweep --config 2 --nq 1 --int8     # ... with int8 elimination rounds
     python -m paper_2602_02827_amd.sweep --config 2 --alpha 0.05 0.1 0.2 0.5 1.0 \
         --gamma 0.05 0.1 0.2 0.3 0.5 0.7 0.9 1.0 --tau 0.4 0.5 0.6 0.7 0.8 0.9  # quality-coverage frontier
+    python -m paper_2602_02827_amd.sweep --doc-length 16 32 48 106 512 4096 65536  # cost of document ends
 
 Prints one JSON line per (K, alpha_ef, M): batch latency of colbandit_full_maxsim and of
 colbandit_topk (events around `--reps` back-to-back asynchronous calls), coverage
@@ -17,7 +18,11 @@ with the same Overlap@K and their coverage (ceil(gamma T)/T, mean k/T).  `--inte
 traces the first Q queries of every Col-Bandit setting and counts how often the exhaustive score
 of a live document lies outside its decision interval [LCB, UCB] (Theorem 1 and the remark on its
 scope: at alpha_ef = 1 the intervals hold jointly with probability 1 - delta only up to the
-simplified radius; at alpha_ef < 1 misses are expected).  The grid of alpha_ef x K follows the knob sweeps of
+simplified radius; at alpha_ef < 1 misses are expected).  `--doc-length L ...` runs nothing of
+the above: it times the exhaustive scoring kernel on 53 M random bf16 tokens (the token count of
+configuration 3, 128 queries x 32 tokens, d = 128) cut into documents of one length L each, one
+JSON line per L; the work per token is the same for every L, so the differences are the cost of
+the document boundaries.  The grid of alpha_ef x K follows the knob sweeps of
 the paper's evaluation (Sec. 5, implementation appendix "Default parameter setting").
 """
 from __future__ import annotations
@@ -25,6 +30,41 @@ from __future__ import annotations
 import argparse
 import json
 import sys
+
+
+def doc_length_sweep(lengths, reps, d):
+    """Exhaustive scoring kernel (Eq. (1)-(3)) against the document length at a fixed token count."""
+    import torch
+    from . import binding as B
+
+    nq, T, total = 128, 32, 53_000_000
+    g = torch.Generator(device="cuda").manual_seed(1)
+    docs = torch.empty((total, d), dtype=torch.bfloat16, device="cuda")
+    for i in range(0, total, 1 << 22):
+        n = min(1 << 22, total - i)
+        docs[i:i + n] = torch.randn((n, d), generator=g, device="cuda").to(torch.bfloat16)
+    Q = torch.randn((nq, T, d), generator=g, device="cuda").to(torch.bfloat16)
+    for L in lengths:
+        N = total // L
+        off = torch.arange(N + 1, dtype=torch.int64, device="cuda") * L
+        tok = N * L
+        ws = B.new_workspace(nq, T, d, N, tok, "cuda")
+        out = {"scores": torch.empty((nq, N), dtype=torch.float32, device="cuda"),
+               "topk_ids": torch.empty((nq, 5), dtype=torch.int64, device="cuda"),
+               "topk_scores": torch.empty((nq, 5), dtype=torch.float32, device="cuda")}
+        for _ in range(2):
+            B.colbandit_full_maxsim(Q, docs[:tok], off, K=5, workspace=ws, out=out)
+        torch.cuda.synchronize()
+        ms = [B.colbandit_full_maxsim(Q, docs[:tok], off, K=5, workspace=ws, out=out,
+                                      want_phase_ms=True)["phase_ms"][0] for _ in range(max(reps, 1))]
+        mean = sum(ms) / len(ms)
+        flops = 2.0 * nq * T * d * tok
+        print(json.dumps({"doc_length": L, "N": N, "tokens": tok, "nq": nq, "T": T, "d": d,
+                          "ms_scoring_kernel": [round(m, 3) for m in ms],
+                          "tflops": round(flops / mean / 1e9, 1),
+                          "frac_of_bf16_mfma_peak": round(flops / mean / 1e9 / 2500.0, 4)}), flush=True)
+        del ws, out
+    return 0
 
 
 def main(argv=None):
@@ -47,6 +87,8 @@ def main(argv=None):
     ap.add_argument("--interval-miss", type=int, default=0, metavar="Q",
                     help="trace the first Q queries and count live documents whose exhaustive score "
                          "leaves [LCB, UCB]")
+    ap.add_argument("--doc-length", type=int, nargs="+", default=[], metavar="L",
+                    help="time the exhaustive kernel on 53 M random tokens cut into documents of L tokens")
     args = ap.parse_args(argv)
 
     import numpy as np
@@ -55,6 +97,8 @@ def main(argv=None):
 
     assert torch.cuda.is_available(), "sweep needs a GPU"
     B.lib()
+    if args.doc_length:
+        return doc_length_sweep(args.doc_length, args.reps, args.d)
     w = synth.config(args.config, device="cuda", scale=args.scale, nq=args.nq, d=args.d)
     nq, T, d, N, total = w.nq, w.T, w.d, w.N, w.total_tokens
     ws = B.new_workspace(nq, T, d, N, total, "cuda")
