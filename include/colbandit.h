@@ -59,7 +59,11 @@ enum {
                                         than the library's built-in buffer holds       */
 };
 
-/* Limits of this build (requests beyond them return COLBANDIT_ERR_UNSUPPORTED). */
+/* Limits of this build (requests beyond them return COLBANDIT_ERR_UNSUPPORTED).
+ * Embedding width d: 32, 64, 96 or 128.  The corpus-streaming kernels and the int8 codes
+ * cover 64 and 128; at 32 and 96 every pass runs on the per-pair gather kernels (same
+ * results, lower throughput) and opts.docs_i8 / colbandit_coarse_maxsim are refused.
+ * Query tokens T: up to COLBANDIT_MAX_T for bf16, up to 64 for fp32. */
 #define COLBANDIT_MAX_T 128          /* query tokens                                  */
 #define COLBANDIT_MAX_K 1024         /* size of the returned top-K                    */
 #define COLBANDIT_MAX_B 16           /* cells revealed per document per round         */

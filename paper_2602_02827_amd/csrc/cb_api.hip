@@ -104,7 +104,7 @@ int check_shapes(const void* Q, int nq, int T, int d, int dt, const void* docs,
     if (dt != COLBANDIT_F32 && dt != COLBANDIT_BF16) return COLBANDIT_ERR_SHAPE;
     // the selection kernels index a list a few chunks (of up to 16,384 entries) past its end
     if (N > 0x7fffffff - (1 << 17) || nq > 65535) return COLBANDIT_ERR_UNSUPPORTED;
-    if (d != 64 && d != 128) return COLBANDIT_ERR_UNSUPPORTED;
+    if (d != 32 && d != 64 && d != 96 && d != 128) return COLBANDIT_ERR_UNSUPPORTED;
     if (T > (dt == COLBANDIT_BF16 ? COLBANDIT_MAX_T : 64)) return COLBANDIT_ERR_UNSUPPORTED;
     if (((uintptr_t)Q & 15) || ((uintptr_t)docs & 15) || ((uintptr_t)off & 7))
         return COLBANDIT_ERR_ALIGNMENT;
@@ -602,6 +602,7 @@ static int topk_impl(const void* Q, int n_queries, int T, int d, colbandit_dtype
         later_rounds = opts->later_rounds;
         if (opts->docs_i8) {
             if (!opts->docs_scale) return COLBANDIT_ERR_NULL;
+            if (d % 64 != 0) return COLBANDIT_ERR_UNSUPPORTED;   // int8 MFMA contracts 64 at a time
             if (((uintptr_t)opts->docs_i8 & 15) || ((uintptr_t)opts->docs_scale & 3))
                 return COLBANDIT_ERR_ALIGNMENT;
             if (opts->coarse_permille < 0 || opts->coarse_permille > 1000) return COLBANDIT_ERR_KNOB;

@@ -328,6 +328,11 @@ static hipError_t gather_by_d(const GatherArgs& A, int mode, const Problem& P, i
                               hipStream_t st) {
     if (P.d == 128) return gather_dispatch<Tag, 128>(A, mode, P.nq, max_count, st);
     if (P.d == 64) return gather_dispatch<Tag, 64>(A, mode, P.nq, max_count, st);
+    // widths that only the gather kernels cover (the int8 MFMA contracts 64 elements at a time)
+    if constexpr (!__is_same(Tag, i8_tag)) {
+        if (P.d == 96) return gather_dispatch<Tag, 96>(A, mode, P.nq, max_count, st);
+        if (P.d == 32) return gather_dispatch<Tag, 32>(A, mode, P.nq, max_count, st);
+    }
     return hipErrorInvalidValue;
 }
 

@@ -118,6 +118,10 @@ def test_coarse_pass_argument_errors(B):
     assert _call_topk(B, opts=B.ColbanditOpts(docs_i8=0x7000, docs_scale=0x8002)) == -6
     assert _call_topk(B, opts=B.ColbanditOpts(docs_i8=0x7000, docs_scale=0x8000, coarse_permille=1001)) == -3
     assert _call_topk(B, opts=B.ColbanditOpts(docs_i8=0x7000, docs_scale=0x8000, coarse_permille=-1)) == -3
+    # int8 codes need a width the int8 matrix instruction covers (multiples of 64)
+    assert _call_topk(B, d=96, opts=B.ColbanditOpts(docs_i8=0x7000, docs_scale=0x8000)) == -4
+    assert _call_topk(B, d=32, opts=B.ColbanditOpts(docs_i8=0x7000, docs_scale=0x8000)) == -4
+    assert _call_topk(B, d=48) == -4 and _call_topk(B, d=256) == -4
 
     # colbandit_quantize_i8
     L = B.lib()
@@ -165,7 +169,7 @@ def test_baseline_argument_errors(B):
     assert uni(K=3) == -1                               # K > 0 needs the top-K outputs
     assert uni(K=11) == -2 and uni(N=0) == -2 and uni(dt=7) == -2
     assert uni(m=0) == -3 and uni(m=33) == -3
-    assert uni(T=65, m=4) == -4 and uni(d=96) == -4
+    assert uni(T=65, m=4) == -4 and uni(d=48) == -4 and uni(d=160) == -4
     assert uni(masks=0x5004) == -6 and uni(Q=0x1008) == -6
     assert uni(ws=None) == -1 and uni(wsb=1024) == -5
     assert L.colbandit_doc_uniform_workspace_bytes(0, 32, 128, 10, 400) == 0

@@ -81,7 +81,7 @@ def test_full_maxsim_fp32_config1(B, S, oracle_mod):
 
 @pytest.mark.parametrize("nq,T,d", [(1, 32, 128), (3, 32, 128), (6, 24, 128), (20, 32, 128),
                                      (5, 7, 128), (3, 40, 128), (2, 100, 128), (4, 32, 64),
-                                     (40, 16, 64)])
+                                     (40, 16, 64), (4, 32, 96), (3, 24, 32), (2, 100, 96)])
 def test_full_maxsim_bf16_dense_ragged(B, S, oracle_mod, nq, T, d):
     # lengths span 1 token, block edges (15/16/17), stage edges (63/64/65), ring wrap (>256)
     # and documents longer than a workgroup's token chunk (4096)
@@ -104,7 +104,7 @@ def test_full_maxsim_bf16_dense_ragged(B, S, oracle_mod, nq, T, d):
 def test_full_maxsim_fp32_ragged_and_d64(B, S, oracle_mod):
     rng = np.random.default_rng(5)
     lengths = [1, 16, 17, 300] + rng.integers(1, 90, 120).tolist()
-    for d, T in [(128, 32), (64, 24), (128, 50)]:
+    for d, T in [(128, 32), (64, 24), (128, 50), (96, 32), (32, 40)]:
         w = _custom(S, lengths, 3, T, d, "f32", 11)
         H, Sor = _oracle_scores(oracle_mod, w)
         r = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=4, want_cells=True)
@@ -533,6 +533,8 @@ def test_colbandit_small_candidate_sets(B, S, oracle_mod):
     (2, 100, 128, 300, 5, 5, 7, 1.0, True),         # int8 rounds, 7 tiles of query tokens
     (4, 32, 128, 6, 5, 5, 4, 0.2, True),            # N <= K + M: no round at all
     (2, 64, 128, 300, 5, 5, 1, 0.6, False),         # one token per round: the 64-round limit
+    (3, 32, 96, 400, 5, 5, 4, 0.3, False),          # widths that only the gather kernels cover
+    (2, 24, 32, 300, 3, 2, 4, 0.5, False),
 ])
 def test_colbandit_corner_shapes(B, S, oracle_mod, nq, T, d, N, K, M, Bsz, alpha, coarse):
     rng = np.random.default_rng(N + T)
@@ -746,7 +748,8 @@ def _clustered_queries(w, S, n_dir, noise, seed):
 @pytest.mark.parametrize("dtype,nq,T,d,m", [("bf16", 3, 32, 128, 4), ("bf16", 20, 32, 128, 13),
                                             ("bf16", 2, 64, 128, 64), ("bf16", 5, 7, 64, 1),
                                             ("bf16", 4, 30, 128, 30), ("f32", 2, 32, 128, 8),
-                                            ("f32", 3, 24, 64, 5)])
+                                            ("f32", 3, 24, 64, 5), ("bf16", 3, 32, 96, 5),
+                                            ("f32", 2, 24, 32, 7)])
 def test_doc_uniform_masks_scores_and_topk_match_oracle(B, S, oracle_mod, dtype, nq, T, d, m):
     """Doc-Uniform (appendix "Compared Methods"): the per-document token subsets are the oracle's
     bit for bit (same counter-based generator, implemented on each side), the partial row sums
@@ -780,7 +783,8 @@ def test_doc_uniform_masks_scores_and_topk_match_oracle(B, S, oracle_mod, dtype,
                                               ("bf16", 6, 32, 128, 0.4), ("bf16", 2, 64, 128, 0.8),
                                               ("bf16", 5, 7, 64, 0.6), ("bf16", 4, 30, 128, 1.0),
                                               ("bf16", 1, 1, 128, 0.5), ("f32", 2, 32, 128, 0.7),
-                                              ("f32", 3, 24, 64, 0.5)])
+                                              ("f32", 3, 24, 64, 0.5), ("bf16", 3, 32, 96, 0.7),
+                                              ("f32", 2, 24, 32, 0.6)])
 def test_ball_carving_clusters_centroids_scores_match_oracle(B, S, oracle_mod, dtype, nq, T, d, tau):
     """Ball-carving (appendix "Compared Methods"): cluster labels and cluster counts are exact
     (the membership test is taken in the same double-precision form on both sides), the
