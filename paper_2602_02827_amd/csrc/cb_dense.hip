@@ -26,9 +26,6 @@
 namespace cb {
 
 constexpr int DENSE_THREADS = 256;
-#ifndef CB_TWO_IN_FLIGHT
-#define CB_TWO_IN_FLIGHT 0
-#endif
 // Ring geometry: four stages.  Kernels with few column tiles per wavefront (small query
 // batches: bound by memory, little register use) take 32-row stages, so that four workgroups fit
 // a CU instead of two and more wavefronts hide the latencies; the others take 64-row stages.
@@ -76,14 +73,10 @@ void k_dense(DenseArgs A) {
     constexpr bool CODES = !__is_same(V, float);
     constexpr int ROWB = D * F::ELEM_BYTES;   // bytes per token row
     constexpr int NCH = ROWB / 16;         // 16-byte pieces per row
-    constexpr bool TWO_IN_FLIGHT = CB_TWO_IN_FLIGHT;
-#ifndef CB_REVEAL_NT
-#define CB_REVEAL_NT 1
-#endif
     // Cache policy of the token copies.  The reveal pass normally has one column group: a token
     // row is read once and should not push the lines of the (sum, M2) array, which fill up over
     // several documents, out of L2; its copies carry the non-temporal hint (bit 1).
-    constexpr int LOAD_POLICY = (REVEAL && CB_REVEAL_NT) ? 2 : 0;
+    constexpr int LOAD_POLICY = REVEAL ? 2 : 0;
     // Swizzle key of a ring row: rows whose 16-byte pieces would fall on the same banks
     // (row stride ROWB against the 256-byte bank window) get different keys.
     constexpr int KEY_SHIFT = NCH >= 16 ? 0 : (NCH == 8 ? 1 : 2);
@@ -287,26 +280,19 @@ void k_dense(DenseArgs A) {
 
     // ---- stage bookkeeping.  The reader walks the chunk stage by stage; when it enters stage st
     // the stages up to st+1 are visible to every wavefront (the first block of st+1 is read as
-    // the "next block" while the last block of st is multiplied) and the following stage (or
-    // two) is in flight.  All four wavefronts walk the same blocks, so they reach stage_enter at
+    // the "next block" while the last block of st is multiplied) and the following stage is in
+    // flight.  All four wavefronts walk the same blocks, so they reach stage_enter at
     // the same points and its barrier matches up.
     // Slot safety: a stage is requested into the slot of a stage at least two behind the
     // reader, which no wavefront reads any more once all have passed the barrier.
     const int nst = (ntok + STAGE_ROWS - 1) / STAGE_ROWS;
     const int nfull = ntok / STAGE_ROWS;            // stages with all their rows
-    // wait until the copies of every stage but the most recently requested one have landed.  A
-    // complete stage is LOADS_PER_WAVE copies per wavefront and loads retire in order, so "at
-    // most LOADS_PER_WAVE outstanding" says exactly that; an incomplete (last) stage may have
-    // issued fewer, then everything is awaited.
-    auto wait_older = [&](int latest) {
-        constexpr int WAIT_KEEP = 0x0F70 | (LOADS_PER_WAVE & 0xF) | ((LOADS_PER_WAVE >> 4) << 14);
-        if (TWO_IN_FLIGHT && latest < nfull) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
-        else __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    };
+    // wait until this wavefront's copies have landed (keeping a second stage in flight across
+    // the barrier was measured and gained nothing)
+    auto wait_copies = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */ };
     // Workgroup barrier without a memory fence: the copies a wavefront is responsible for have
-    // been awaited explicitly just before, every ring read of the slot that is about to be
-    // overwritten has been consumed by its MFMAs, and younger copies may stay in flight across
-    // the barrier.  The empty asm statements keep the compiler from moving ring accesses across.
+    // been awaited explicitly just before and every ring read of the slot that is about to be
+    // overwritten has been consumed by its MFMAs.  The empty asm statements keep the compiler from moving ring accesses across.
     auto ring_barrier = [&]() {
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
@@ -314,21 +300,15 @@ void k_dense(DenseArgs A) {
     };
     stage_fetch(0);
     if (nst > 1) stage_fetch(1);
-    if (TWO_IN_FLIGHT && nst > 2) stage_fetch(2);
-    wait_older(TWO_IN_FLIGHT && nst > 2 ? 2 : nst);
+    wait_copies();
     ring_barrier();
-    if (TWO_IN_FLIGHT) {
-        if (nst > 3) stage_fetch(3);
-    } else if (nst > 2) {
-        stage_fetch(2);
-    }
+    if (nst > 2) stage_fetch(2);
     // the reader enters stage st >= 1: publish stage st+1, request the next one
     auto stage_enter = [&](int st) {
         if (st + 1 >= nst) return;                  // everything is visible already
-        wait_older(st + 2 < nst ? st + 2 : nst);
+        wait_copies();
         ring_barrier();
-        const int req = TWO_IN_FLIGHT ? st + 3 : st + 2;
-        if (req < nst) stage_fetch(req);
+        if (st + 2 < nst) stage_fetch(st + 2);
     };
 
     // ---- block stream.  The chunk's tokens are one stream cut into aligned blocks of 16 rows,
@@ -418,7 +398,7 @@ void k_dense(DenseArgs A) {
     constexpr bool TIGHT_RUNS = NT >= 8;
     const int tight_end = TIGHT_RUNS ? (nfull - 2) * STAGE_ROWS : 0;
     auto stage_enter_full = [&](int bs) {        // bs < tight_end is a stage boundary
-        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+        wait_copies();
         ring_barrier();
 #pragma unroll
         for (int i = 0; i < LOADS_PER_WAVE; ++i) {
@@ -434,7 +414,7 @@ void k_dense(DenseArgs A) {
     int bs = 0;
     load_block(a0, 0);
     while (bs < ntok) {
-        if (TIGHT_RUNS && !TWO_IN_FLIGHT && bs < tight_end) {
+        if (TIGHT_RUNS && bs < tight_end) {
             // blocks from bs on that end before the current document does
             int run = doc < i1 ? (dend - bs - 1) >> 4 : RING_ROWS;
             const int left = (tight_end - bs) >> 4;
