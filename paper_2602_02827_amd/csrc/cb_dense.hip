@@ -73,10 +73,11 @@ void k_dense(DenseArgs A) {
     constexpr bool CODES = !__is_same(V, float);
     constexpr int ROWB = D * F::ELEM_BYTES;   // bytes per token row
     constexpr int NCH = ROWB / 16;         // 16-byte pieces per row
-    // Cache policy of the token copies.  The reveal pass normally has one column group: a token
-    // row is read once and should not push the lines of the (sum, M2) array, which fill up over
-    // several documents, out of L2; its copies carry the non-temporal hint (bit 1).
-    constexpr int LOAD_POLICY = REVEAL ? 2 : 0;
+    // Cache policy of the token copies.  The reveal pass normally has one column group, and the
+    // score kernels with at most four column tiles per wavefront always have: a token row is read
+    // once and should not push other lines out of L2 - above all those of the (sum, M2) array,
+    // which fill up over several documents; such copies carry the non-temporal hint (bit 1).
+    constexpr int LOAD_POLICY = (REVEAL || NT <= 4) ? 2 : 0;
     // Swizzle key of a ring row: rows whose 16-byte pieces would fall on the same banks
     // (row stride ROWB against the 256-byte bank window) get different keys.
     constexpr int KEY_SHIFT = NCH >= 16 ? 0 : (NCH == 8 ? 1 : 2);
