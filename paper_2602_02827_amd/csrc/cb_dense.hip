@@ -372,7 +372,8 @@ void k_dense(DenseArgs A) {
 #pragma unroll
             for (int tt = 0; tt < NT; ++tt) hB[tt] = lowest_val<V>();
             const int bb = b < lo ? lo : b;     // offsets that run backwards: an empty part
-            block_mma_split<NT>(a, bq, h, hB, lo, bb, rowbase);
+            if (NT >= 8 && lo == 0 && bb >= 1 && bb <= 15) block_mma_split_rows<NT>(a, bq, h, hB, bb);
+            else block_mma_split<NT>(a, bq, h, hB, lo, bb, rowbase);
             finalize(doc);
             ++doc;
             if (doc >= i1) return;

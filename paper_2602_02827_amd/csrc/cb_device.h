@@ -244,6 +244,118 @@ __device__ __forceinline__ void block_mma_split(const F& a, const F (&bq)[NT],
 }
 
 // ---------------------------------------------------------------------------------
+// The split fold with the boundary known at compile time.  A block's 16 rows are four row
+// groups of four (row group = lane >> 4 = a DPP row); rows [0, b) belong to the ending
+// document, rows [b, 16) to the next one.  With KB = b / 4 and KR = b % 4 fixed, whole row
+// groups are folded by one maximum that writes only the DPP rows named by an immediate row
+// mask, and the one group that straddles the boundary (KR > 0) takes the maxima of its first
+// KR and its last 4 - KR rows.  dpp_max<RM>(h, x): h <- max(h, x) in the rows of RM, h elsewhere
+// (a DPP move whose disabled rows keep the identity of the maximum, then the maximum: the
+// compiler merges the two into one v_max_*_dpp).
+// ---------------------------------------------------------------------------------
+template <int RM> __device__ __forceinline__ float dpp_max(float h, float x) {
+    if constexpr (RM == 0) return h;
+    else if constexpr (RM == 0xF) return fmaxf(h, x);
+    else {
+        const int low = __builtin_bit_cast(int, -__builtin_inff());
+        const int y = __builtin_amdgcn_update_dpp(low, __builtin_bit_cast(int, x), 0xE4, RM, 0xF, false);
+        return fmaxf(h, __builtin_bit_cast(float, y));
+    }
+}
+template <int RM> __device__ __forceinline__ int dpp_max(int h, int x) {
+    if constexpr (RM == 0) return h;
+    else if constexpr (RM == 0xF) return h > x ? h : x;
+    else {
+        const int y = __builtin_amdgcn_update_dpp((int)0x80000000, x, 0xE4, RM, 0xF, false);
+        return h > y ? h : y;
+    }
+}
+template <int KB, int KR, class V, class ACC>
+__device__ __forceinline__ void fold_split_at(V& hA, V& hB, const ACC& c) {
+    constexpr int RM_A = (1 << KB) - 1;                         // row groups wholly before b
+    constexpr int RM_S = KR > 0 ? (1 << KB) : 0;                // the straddling row group
+    constexpr int RM_B = 0xF & ~(RM_A | RM_S);                  // row groups wholly from b on
+    V sA, sB, all;
+    if constexpr (KR == 0) {
+        all = vmax(vmax(vmax(c[0], c[1]), c[2]), c[3]);
+        sA = sB = all;
+    } else if constexpr (KR == 1) {
+        sA = c[0];
+        sB = vmax(vmax(c[1], c[2]), c[3]);
+        all = vmax(sA, sB);
+    } else if constexpr (KR == 2) {
+        sA = vmax(c[0], c[1]);
+        sB = vmax(c[2], c[3]);
+        all = vmax(sA, sB);
+    } else {
+        sA = vmax(vmax(c[0], c[1]), c[2]);
+        sB = c[3];
+        all = vmax(sA, sB);
+    }
+    if constexpr (__is_same(V, float)) {
+        // Written out: the compiler merges the move and the maximum only for integers.  sA, sB
+        // and `all` were written by vector instructions just before; a DPP operand may be read
+        // two wait states after such a write at the earliest, hence the s_nop.  Row masks of
+        // zero (no such row group) make the instruction a no-op.
+        if constexpr (KR > 0) {
+            asm("s_nop 1\n\t"
+                "v_max_f32_dpp %0, %2, %0 quad_perm:[0,1,2,3] row_mask:%5 bank_mask:0xf\n\t"
+                "v_max_f32_dpp %1, %2, %1 quad_perm:[0,1,2,3] row_mask:%6 bank_mask:0xf\n\t"
+                "v_max_f32_dpp %0, %3, %0 quad_perm:[0,1,2,3] row_mask:%7 bank_mask:0xf\n\t"
+                "v_max_f32_dpp %1, %4, %1 quad_perm:[0,1,2,3] row_mask:%7 bank_mask:0xf"
+                : "+v"(hA), "+v"(hB)
+                : "v"(all), "v"(sA), "v"(sB), "n"(RM_A), "n"(RM_B), "n"(RM_S));
+        } else {
+            asm("s_nop 1\n\t"
+                "v_max_f32_dpp %0, %2, %0 quad_perm:[0,1,2,3] row_mask:%3 bank_mask:0xf\n\t"
+                "v_max_f32_dpp %1, %2, %1 quad_perm:[0,1,2,3] row_mask:%4 bank_mask:0xf"
+                : "+v"(hA), "+v"(hB)
+                : "v"(all), "n"(RM_A), "n"(RM_B));
+        }
+    } else {
+        hA = dpp_max<RM_A>(hA, all);
+        hB = dpp_max<RM_B>(hB, all);
+        if constexpr (KR > 0) {
+            hA = dpp_max<RM_S>(hA, sA);
+            hB = dpp_max<RM_S>(hB, sB);
+        }
+    }
+}
+// block_mma_split for rows [0, b) / [b, 16), b = 4 * KB + KR in 1..15
+template <int NT, int KB, int KR, class F>
+__device__ __forceinline__ void block_mma_split_at(const F& a, const F (&bq)[NT],
+                                                   typename F::val_t (&hA)[NT],
+                                                   typename F::val_t (&hB)[NT]) {
+    using acc_t = typename F::acc_t;
+    if constexpr (NT == 1) {
+        acc_t acc = {0, 0, 0, 0};
+        F::mma(acc, a, bq[0]);
+        fold_split_at<KB, KR>(hA[0], hB[0], acc);
+    } else {
+#pragma unroll
+        for (int p = 0; p < NT / 2; ++p) {
+            acc_t c0 = {0, 0, 0, 0}, c1 = c0;
+            F::mma2(c0, c1, a, bq[2 * p], bq[2 * p + 1]);
+            fold_split_at<KB, KR>(hA[2 * p], hB[2 * p], c0);
+            fold_split_at<KB, KR>(hA[2 * p + 1], hB[2 * p + 1], c1);
+        }
+    }
+}
+template <int NT, class F>
+__device__ __forceinline__ void block_mma_split_rows(const F& a, const F (&bq)[NT],
+                                                     typename F::val_t (&hA)[NT],
+                                                     typename F::val_t (&hB)[NT], int b) {
+    switch (b) {
+#define CB_SPLIT_CASE(B) case B: block_mma_split_at<NT, (B) / 4, (B) % 4>(a, bq, hA, hB); break;
+        CB_SPLIT_CASE(1) CB_SPLIT_CASE(2) CB_SPLIT_CASE(3) CB_SPLIT_CASE(4) CB_SPLIT_CASE(5)
+        CB_SPLIT_CASE(6) CB_SPLIT_CASE(7) CB_SPLIT_CASE(8) CB_SPLIT_CASE(9) CB_SPLIT_CASE(10)
+        CB_SPLIT_CASE(11) CB_SPLIT_CASE(12) CB_SPLIT_CASE(13) CB_SPLIT_CASE(14) CB_SPLIT_CASE(15)
+#undef CB_SPLIT_CASE
+        default: break;
+    }
+}
+
+// ---------------------------------------------------------------------------------
 // Cross-lane helpers.  A wavefront is four rows of 16 lanes; row = lane >> 4 is the
 // accumulator's row group, col = lane & 15 its column.  DPP moves data inside a row,
 // v_permlane32_swap / v_permlane16_swap exchange rows between two registers:

@@ -700,6 +700,54 @@ def test_coarse_maxsim_cells_are_the_integer_maxima(B, S, oracle_mod, nq, T, d):
     np.testing.assert_allclose(cm["scores"].cpu().numpy(), cells.sum(axis=2), rtol=1e-5, atol=1e-5)
 
 
+def test_every_position_of_a_document_end_inside_a_block(B, S, oracle_mod):
+    """The wide dense kernels fold a block in which a document ends by code specialised for the
+    row at which it ends; here every such row 1..15 occurs (a document of b tokens from a block
+    start, then one of 32 - b tokens that ends with a block), and two and three ends in one
+    block (which take the general fold).  Exhaustive cells (bf16, 20 queries: eight column tiles
+    per wavefront), integer cells of the int8 codes, and the round-1 statistics of Col-Bandit
+    over 72 queries (eight tiles per wavefront in the reveal pass) against the oracle."""
+    lengths = []
+    for b in range(1, 16):
+        lengths += [b, 32 - b]
+    lengths += [3, 4, 9, 5, 5, 6, 16, 1, 1, 1, 13] + list(range(1, 40))
+    nq, T, d = 20, 32, 128
+    w = _custom(S, lengths, nq, T, d, "bf16", 77)
+    H, Sor = _oracle_scores(oracle_mod, w)
+    r = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=3, want_cells=True)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(r["cells"].cpu().numpy(), H, rtol=TOL["bf16"], atol=1e-5)
+    np.testing.assert_allclose(r["scores"].cpu().numpy(), Sor, rtol=TOL["bf16"], atol=1e-4)
+    # int8 codes: exact integer maxima
+    d8, ds = B.colbandit_quantize_i8(w.docs)
+    cm = B.colbandit_coarse_maxsim(w.Q, d8, ds, w.offsets, want_cells=True)
+    torch.cuda.synchronize()
+    q8, qs = cm["q_codes"].cpu().numpy(), cm["q_scales"].cpu().numpy()
+    off, D8 = w.offsets.cpu().numpy(), d8.cpu().numpy()
+    sd = np.float32(ds.cpu().numpy()[0])
+    for q in (0, 7, 19):
+        _, Hint = oracle_mod.maxsim_cells_i8(q8[q], qs[q], D8, sd, off)
+        np.testing.assert_array_equal(cm["cells"][q].cpu().numpy(),
+                                      Hint.astype(np.float32) * (np.float32(qs[q]) * sd))
+    # the reveal pass with eight tiles per wavefront: 72 queries x 4 revealed tokens
+    w2 = _custom(S, lengths, 72, T, d, "bf16", 78)
+    full = B.colbandit_full_maxsim(w2.Q, w2.docs, w2.offsets, K=0, want_cells=True)
+    res = B.colbandit_topk(w2.Q, w2.docs, w2.offsets, 3, 1.0, 0.01, 2, 9, B=4, trace=True)
+    e8, es = B.colbandit_quantize_i8(w2.docs)
+    res8 = B.colbandit_topk(w2.Q, w2.docs, w2.offsets, 3, 1.0, 0.01, 2, 9, B=4, trace=True,
+                            docs_i8=e8, docs_scale=es)
+    cm2 = B.colbandit_coarse_maxsim(w2.Q, e8, es, w2.offsets, want_cells=True)
+    torch.cuda.synchronize()
+    for q in (0, 35, 71):
+        Hq = full["cells"][q].cpu().numpy().astype(np.float64)
+        Hc = cm2["cells"][q].cpu().numpy().astype(np.float64)
+        pi = B.colbandit_permutation(9, q, T)
+        div, orc = _compare_rounds(oracle_mod, res["trace"], q, Hq, 3, 2, 4, 1.0, 0.01, pi)
+        assert res["stats"][q]["rounds"] == orc.rounds
+        div, orc = _compare_rounds(oracle_mod, res8["trace"], q, Hc, 3, 2, 4, 1.0, 0.01, pi, Hexact=Hq)
+        assert res8["stats"][q]["rounds"] == orc.rounds
+
+
 @pytest.mark.parametrize("alpha,K,M,Bsz", [(0.2, 5, 5, 4), (1.0, 5, 5, 4), (0.5, 10, 5, 3), (0.2, 5, 0, 16)])
 def test_colbandit_on_int8_codes_rounds_match_oracle(B, S, oracle_mod, alpha, K, M, Bsz):
     """Rounds decided on coarse cells, survivors rescored exactly (implementation appendix):
