@@ -1,4 +1,4 @@
-// Dense corpus-streaming MaxSim kernel for bf16 (gfx950).
+// Dense corpus-streaming MaxSim kernel for bf16 embeddings and int8 codes (gfx950).
 //
 // Shape of the work: a [tokens x d] corpus against a few thousand query rows, d = 64/128.
 // The result matrix is never written; each 16x16 MFMA tile is folded at once into a
@@ -18,9 +18,12 @@
 //   * The chunk's tokens form one stream of aligned 16-token blocks, whatever the document
 //     boundaries, so no token is multiplied twice.  A block inside one document folds into
 //     the running maxima directly; where a document ends inside a block the fold is split
-//     by accumulator row (block_mma_split).  Documents of any length >= 1 are handled.
+//     by accumulator row (block_mma_split_rows / block_mma_split).  Documents of any length
+//     >= 1 are handled.  Runs of whole blocks inside one document go through a loop that holds
+//     only operand reads and MFMAs.
 //   * Workgroup ids are laid out so that the column groups of one token chunk run on the
-//     same XCD and share its L2.
+//     same XCD and share its L2; eight consecutive chunks go to the eight XCDs in a rotating
+//     order.
 #include "cb_launch.h"
 
 namespace cb {
@@ -372,6 +375,8 @@ void k_dense(DenseArgs A) {
 #pragma unroll
             for (int tt = 0; tt < NT; ++tt) hB[tt] = lowest_val<V>();
             const int bb = b < lo ? lo : b;     // offsets that run backwards: an empty part
+            // the usual case - one document end in the block - takes the fold specialised by the
+            // row of the end (the wide kernels only: it is 15 copies of the block's code)
             if (NT >= 8 && lo == 0 && bb >= 1 && bb <= 15) block_mma_split_rows<NT>(a, bq, h, hB, bb);
             else block_mma_split<NT>(a, bq, h, hB, lo, bb, rowbase);
             finalize(doc);
