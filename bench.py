@@ -50,10 +50,14 @@ def kernel_source_hash():
     return h.hexdigest()[:16]
 
 
-def measured_traffic(workload_key):
+def measured_traffic(workload_key, field="calibrated"):
     """{kernel label: HBM bytes per launch} from the counter summary, or {} if it was taken on
     other kernel sources or another workload.  Line format of the file:
-    record <label> workload=<key> sources=<hash> fetch_kib=<x> write_kib=<y> fetch_scale=<a> write_scale=<b>"""
+    record <label> workload=<key> sources=<hash> fetch_kib=<x> write_kib=<y> fetch_scale=<a> write_scale=<b>
+        [rd32=<n> rd64=<n> rd128=<n> wr32=<n> wr64=<n>]
+    field "calibrated": FETCH_SIZE and WRITE_SIZE readings times their copy-kernel factors;
+    field "by_request_size": the L2's read and write requests to memory counted by size (the
+    optional fields), bytes = 32 / 64 / 128 per request."""
     out = {}
     if not os.path.exists(TRAFFIC_FILE):
         return out
@@ -65,8 +69,12 @@ def measured_traffic(workload_key):
         kv = dict(x.split("=", 1) for x in f[2:])
         if kv.get("workload") != workload_key or kv.get("sources") != have:
             continue
-        out[f[1]] = 1024.0 * (float(kv["fetch_kib"]) * float(kv["fetch_scale"]) +
-                              float(kv["write_kib"]) * float(kv["write_scale"]))
+        if field == "calibrated":
+            out[f[1]] = 1024.0 * (float(kv["fetch_kib"]) * float(kv["fetch_scale"]) +
+                                  float(kv["write_kib"]) * float(kv["write_scale"]))
+        elif all(k in kv for k in ("rd32", "rd64", "rd128", "wr32", "wr64")):
+            out[f[1]] = (32.0 * float(kv["rd32"]) + 64.0 * float(kv["rd64"]) + 128.0 * float(kv["rd128"]) +
+                         32.0 * float(kv["wr32"]) + 64.0 * float(kv["wr64"]))
     return out
 
 
@@ -312,6 +320,7 @@ def main():
     ms_topk = float(np.mean([m[1] for m in ms_kernel]))
     tflops_kernel = flops_full / (ms_dense * 1e-3) / 1e12
     traffic = measured_traffic("%s/nq%d/N%d/tok%d" % (w.name, nq, N, total))
+    traffic_rs = measured_traffic("%s/nq%d/N%d/tok%d" % (w.name, nq, N, total), "by_request_size")
     dense = w.dtype == "bf16"
     elem = 2 if dense else 4
     roofline = {"bound": "mfma" if dense else "alu",
@@ -319,13 +328,16 @@ def main():
                           else "k_gather (fp32 inputs)",
                 "achieved": round(tflops_kernel, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(tflops_kernel / PEAK_BF16_TFLOPS, 4), "traffic": traffic.get("full_maxsim"),
+                "traffic_by_request_size": traffic_rs.get("full_maxsim"),
                 "ms_per_launch": round(ms_dense, 3),
                 "flops_per_launch": flops_full,
                 "note": "algorithmic flops 2*T*d per (query, document token) x nq x tokens per "
                         "launch, over the kernel's own duration taken by the library with events "
                         "on the launch stream inside the timed steps; the whole call (kernel + "
                         "chunk table + top-K, %.3f ms) runs at %.1f TFLOP/s; traffic = HBM bytes "
-                        "per launch from hardware counters (profiles/hbm_traffic_counters.txt), "
+                        "per launch from hardware counters (profiles/hbm_traffic_counters.txt: "
+                        "FETCH_SIZE and WRITE_SIZE scaled by their readings for a 1 GiB copy; "
+                        "traffic_by_request_size = the L2's memory requests counted by size), "
                         "null unless taken on these kernel sources and this workload"
                         % (ms_full, tflops)}
 
@@ -344,7 +356,8 @@ def main():
                "hbm": {"achieved": round(bytes_r1 / (ms_r1 * 1e-3) / 1e9, 1) if ms_r1 > 0 else None,
                        "peak": PEAK_HBM_GBS, "unit": "GB/s",
                        "frac": round(t_hbm * 1e3 / ms_r1, 4) if ms_r1 > 0 else None,
-                       "bytes": bytes_r1, "traffic": traffic.get("reveal_round1")},
+                       "bytes": bytes_r1, "traffic": traffic.get("reveal_round1"),
+                       "traffic_by_request_size": traffic_rs.get("reveal_round1")},
                "mfma": {"achieved": round(flops_r1 / (ms_r1 * 1e-3) / 1e12, 1) if ms_r1 > 0 else None,
                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(t_mfma * 1e3 / ms_r1, 4) if ms_r1 > 0 else None,
@@ -368,6 +381,7 @@ def main():
               "achieved": gbs(ms_r2), "peak": PEAK_HBM_GBS, "unit": "GB/s",
               "frac": round(gbs(ms_r2) / PEAK_HBM_GBS, 4) if gather_valid else None,
               "traffic": traffic.get("gather_round2"),
+              "traffic_by_request_size": traffic_rs.get("gather_round2"),
               "pairs": pairs2, "bytes": gather_bytes, "ms": round(ms_r2, 3),
               "all_rounds_ge2": {"ms": round(ms_later, 3), "achieved": gbs(ms_later)},
               "corpus_pass_rounds": st[0]["corpus_pass_rounds"],

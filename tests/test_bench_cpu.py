@@ -49,6 +49,11 @@ def test_traffic_records_count_only_for_the_sources_and_workload_they_were_taken
     monkeypatch.setattr(bench, "TRAFFIC_FILE", str(f))
     got = bench.measured_traffic("W1")
     assert got == {"full": 1024.0 * (1000 * 2.0 + 10 * 1.0)}
+    assert bench.measured_traffic("W1", "by_request_size") == {}      # no request counts in the record
+    f.write_text(f.read_text() +
+                 f"record sized workload=W1 sources={have} kernel=k fetch_kib=1 write_kib=1 fetch_scale=2.0 "
+                 "write_scale=1.0 rd32=1 rd64=2 rd128=3 wr32=4 wr64=5\n")
+    assert bench.measured_traffic("W1", "by_request_size") == {"sized": 32.0 + 128 + 384 + 128 + 320}
     assert bench.measured_traffic("W3") == {}
     monkeypatch.setattr(bench, "TRAFFIC_FILE", str(tmp_path / "absent.txt"))
     assert bench.measured_traffic("W1") == {}
