@@ -152,8 +152,13 @@ def main(argv=None):
                                                         want_scores=False, out=full))
         ids_full = full["topk_ids"].cpu().numpy()
         overlap_of = lambda ids: float(np.mean([len(set(ids_full[q]) & set(ids[q])) / K for q in range(nq)]))
+        # the scoring kernel alone (the library's own events), mean of `reps` launches
+        nrep = max(args.reps, 1)
+        ms_kernel = sum(B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=K, workspace=ws, want_scores=False,
+                                                out=full, want_phase_ms=True)["phase_ms"][0]
+                        for _ in range(nrep)) / nrep
         head = {"workload": w.name, "n_queries": nq, "N": N, "T": T, "d": d, "K": K,
-                "full_ms": round(ms_full, 3)}
+                "full_ms": round(ms_full, 3), "full_kernel_ms": round(ms_kernel, 3)}
         if args.gamma:
             wsu = torch.empty(int(B.lib().colbandit_doc_uniform_workspace_bytes(nq, T, d, N, total)),
                               dtype=torch.uint8, device="cuda")
@@ -200,7 +205,7 @@ def main(argv=None):
                 print(json.dumps({
                     "workload": w.name, "n_queries": nq, "N": N, "T": T, "d": d, "K": K,
                     "method": "colbandit", "alpha_ef": alpha,
-                    "M": M, "B": args.B, "reveals": "int8" if args.int8 else w.dtype, "full_ms": round(ms_full, 3), "colbandit_ms": round(ms_cb, 3),
+                    "M": M, "B": args.B, "reveals": "int8" if args.int8 else w.dtype, "full_ms": round(ms_full, 3), "full_kernel_ms": round(ms_kernel, 3), "colbandit_ms": round(ms_cb, 3),
                     "speedup": round(ms_full / ms_cb, 2), "coverage": round(cov, 4),
                     "computed_cells_over_all_cells": round(sum(s["cells_computed"] for s in st) / (float(nq) * N * T), 4),
                     "overlap_at_k": round(overlap, 4),
