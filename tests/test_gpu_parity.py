@@ -101,6 +101,23 @@ def test_full_maxsim_bf16_dense_ragged(B, S, oracle_mod, nq, T, d):
                     TOL["bf16"])
 
 
+def test_documents_much_longer_than_a_token_chunk(B, S, oracle_mod):
+    """Documents of several chunks leave runs of empty chunks behind them (a chunk belongs to the
+    document that starts in it); every workgroup with an empty chunk must exit and the others
+    must cover the long rows - exhaustive cells for a wide and a narrow batch, and the reveal
+    pass through Col-Bandit's first round."""
+    lengths = [20000, 3, 9000, 1, 1, 4096, 4097, 8192, 17, 12289, 40]
+    for nq in (2, 20):
+        w = _custom(S, lengths, nq, 32, 128, "bf16", 5 + nq)
+        H, Sor = _oracle_scores(oracle_mod, w)
+        r = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=3, want_cells=True)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(r["cells"].cpu().numpy(), H, rtol=TOL["bf16"], atol=1e-5)
+        np.testing.assert_allclose(r["scores"].cpu().numpy(), Sor, rtol=TOL["bf16"], atol=1e-4)
+    w = _custom(S, lengths, 3, 32, 128, "bf16", 9)
+    _run_colbandit_case(B, oracle_mod, w, 2, 1, 4, 0.5, seed=3)
+
+
 def test_full_maxsim_fp32_ragged_and_d64(B, S, oracle_mod):
     rng = np.random.default_rng(5)
     lengths = [1, 16, 17, 300] + rng.integers(1, 90, 120).tolist()
