@@ -107,7 +107,7 @@ def test_documents_much_longer_than_a_token_chunk(B, S, oracle_mod):
     must cover the long rows - exhaustive cells for a wide and a narrow batch, and the reveal
     pass through Col-Bandit's first round."""
     lengths = [20000, 3, 9000, 1, 1, 4096, 4097, 8192, 17, 12289, 40]
-    for nq in (2, 20):
+    for nq in (1, 2, 20):       # one query: the wavefronts of a workgroup split the documents
         w = _custom(S, lengths, nq, 32, 128, "bf16", 5 + nq)
         H, Sor = _oracle_scores(oracle_mod, w)
         r = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=3, want_cells=True)
@@ -138,17 +138,18 @@ def test_documents_without_tokens_get_minus_infinity_and_disturb_nothing(B, S, o
     lengths = rng.integers(1, 40, 400).tolist()
     for i in (0, 1, 7, 8, 9, 100, 250, 251, 252, 399):
         lengths[i] = 0
-    w = _custom(S, lengths, 3, 32, 128, "bf16", 43)
-    full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=0)
-    torch.cuda.synchronize()
-    got = full["scores"].cpu().numpy()
-    keep = [i for i, n in enumerate(lengths) if n > 0]
-    E, off = w.host_docs(keep)
-    Qh = w.host_queries()
-    for q in range(w.nq):
-        want = oracle_mod.row_sums(oracle_mod.maxsim_cells(Qh[q], E, off))
-        np.testing.assert_allclose(got[q][keep], want, rtol=TOL["bf16"], atol=1e-4)
-        assert np.all(np.isneginf(got[q][[i for i, n in enumerate(lengths) if n == 0]]))
+    for nq in (3, 1):
+        w = _custom(S, lengths, nq, 32, 128, "bf16", 43)
+        full = B.colbandit_full_maxsim(w.Q, w.docs, w.offsets, K=0)
+        torch.cuda.synchronize()
+        got = full["scores"].cpu().numpy()
+        keep = [i for i, n in enumerate(lengths) if n > 0]
+        E, off = w.host_docs(keep)
+        Qh = w.host_queries()
+        for q in range(w.nq):
+            want = oracle_mod.row_sums(oracle_mod.maxsim_cells(Qh[q], E, off))
+            np.testing.assert_allclose(got[q][keep], want, rtol=TOL["bf16"], atol=1e-4)
+            assert np.all(np.isneginf(got[q][[i for i, n in enumerate(lengths) if n == 0]]))
 
 
 def test_nan_rows_and_token_less_documents_do_not_damage_other_documents(B, S, oracle_mod):
