@@ -65,7 +65,7 @@ struct DenseArgs {
     const float* dscale;
 };
 
-template <typename Tag, int D, int NT, int TQ, bool REVEAL, bool SPLIT_DOCS = false>
+template <typename Tag, int D, int NT, int TQ, bool REVEAL, int SPLIT_DOCS = 0>
 __global__ __launch_bounds__(DENSE_THREADS, (RingShape<NT, D * Frag<Tag, D>::ELEM_BYTES>::MIN_BLOCKS))
 void k_dense(DenseArgs A) {
     using F = Frag<Tag, D>;
@@ -116,16 +116,20 @@ void k_dense(DenseArgs A) {
 
     const int lgG = REVEAL ? 31 - __builtin_clz(A.G > 0 ? A.G : 1) : 0;   // G is a power of two
     // ---- query rows of this wavefront's column tiles -> B fragments (registers)
-    // When every column tile of the launch fits into ONE wavefront's NT tiles (one or two
-    // queries), the other three wavefronts of a workgroup would only repeat its work.  Instead
-    // all four take the same tiles and split the chunk's DOCUMENTS among themselves: a
-    // wavefront multiplies the blocks inside its own documents (every fourth) and every block
-    // in which a document ends, and writes the scores of its own documents only.  All four
-    // still walk the same block stream, so the stage barriers match up.
-    // (SPLIT_DOCS: the launch has one column group.)
-    static_assert(!SPLIT_DOCS || (!REVEAL && NT <= 2), "document splitting is for the smallest score kernels");
-    const int tile0 = SPLIT_DOCS ? 0 : (group * 4 + wave) * NT;
-    auto mine = [&](int doc) { return !SPLIT_DOCS || ((doc - i0) & 3) == wave; };
+    // When the column tiles of the launch fit into one or two of the four wavefronts (one or two
+    // queries), the others would only repeat their work.  Instead SPLIT_DOCS (4 or 2) wavefronts
+    // take the same tiles and split the chunk's DOCUMENTS among themselves: a wavefront
+    // multiplies the blocks inside its own documents (every fourth, or every second) and every
+    // block in which a document ends, and writes the scores of its own documents only.  All four
+    // still walk the same block stream, so the stage barriers match up.  (SPLIT_DOCS: the launch
+    // has one column group.)
+    static_assert(SPLIT_DOCS == 0 || ((SPLIT_DOCS == 2 || SPLIT_DOCS == 4) && !REVEAL && NT <= 2),
+                  "document splitting is for the smallest score kernels");
+    constexpr int TILE_WAVES = SPLIT_DOCS ? 4 / SPLIT_DOCS : 4;      // wavefronts with tiles of their own
+    const int tile0 = SPLIT_DOCS ? (wave % TILE_WAVES) * NT : (group * 4 + wave) * NT;
+    auto mine = [&](int doc) {
+        return SPLIT_DOCS == 0 || ((doc - i0) & (SPLIT_DOCS ? SPLIT_DOCS - 1 : 0)) == wave / TILE_WAVES;
+    };
     F bq[NT];
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt) {
@@ -519,7 +523,7 @@ static void fill_dense(DenseArgs& A, const Problem& P, const Work& W, int n_chun
     A.stat = W.stat;
 }
 
-template <typename Tag, int D, int NT, int TQ, bool REVEAL, bool SPLIT_DOCS = false>
+template <typename Tag, int D, int NT, int TQ, bool REVEAL, int SPLIT_DOCS = 0>
 static hipError_t dense_go(DenseArgs& A, int tiles, hipStream_t st) {
     A.n_groups = SPLIT_DOCS ? 1 : (tiles + 4 * NT - 1) / (4 * NT);
     const int chunks8 = (A.n_chunks + 7) / 8 * 8;
@@ -531,12 +535,11 @@ static hipError_t dense_go(DenseArgs& A, int tiles, hipStream_t st) {
 
 template <typename Tag, int D, int TQ>
 static hipError_t dense_score_nt(DenseArgs& A, int tiles, hipStream_t st) {
-    // a single query (two of at most 16 tokens): its tiles fit one wavefront and the four
-    // wavefronts split the documents: 2.39 -> 2.05 ms for the pass over 13.6 GB.  (With four tiles
-    // per wavefront the same scheme serves two queries, but ran slower than two wavefronts that
-    // hold two tiles each: 2.45 against 2.26 ms.)
+    // one or two queries (twice as many of at most 16 tokens): the tiles fit one or two
+    // wavefronts, and four or two wavefronts split the documents
     if constexpr (TQ <= 2) {
-        if (tiles <= 2) return dense_go<Tag, D, 2, TQ, false, true>(A, tiles, st);
+        if (tiles <= 2) return dense_go<Tag, D, 2, TQ, false, 4>(A, tiles, st);
+        if (tiles <= 4) return dense_go<Tag, D, 2, TQ, false, 2>(A, tiles, st);
     }
     if constexpr (TQ <= 2) {
         if (tiles <= 8) return dense_go<Tag, D, 2, TQ, false>(A, tiles, st);
