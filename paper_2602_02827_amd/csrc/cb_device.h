@@ -295,20 +295,24 @@ __device__ __forceinline__ void fold_split_at(V& hA, V& hB, const ACC& c) {
     if constexpr (__is_same(V, float)) {
         // Written out: the compiler merges the move and the maximum only for integers.  sA, sB
         // and `all` were written by vector instructions just before; a DPP operand may be read
-        // two wait states after such a write at the earliest, hence the s_nop.  Row masks of
-        // zero (no such row group) make the instruction a no-op.
+        // two wait states after such a write at the earliest, hence the leading s_nop; the
+        // trailing one gives whatever the compiler places next (it does not see these writes)
+        // the same distance to hA and hB.  Row masks of zero (no such row group) make the
+        // instruction a no-op.
         if constexpr (KR > 0) {
             asm("s_nop 1\n\t"
                 "v_max_f32_dpp %0, %2, %0 quad_perm:[0,1,2,3] row_mask:%5 bank_mask:0xf\n\t"
                 "v_max_f32_dpp %1, %2, %1 quad_perm:[0,1,2,3] row_mask:%6 bank_mask:0xf\n\t"
                 "v_max_f32_dpp %0, %3, %0 quad_perm:[0,1,2,3] row_mask:%7 bank_mask:0xf\n\t"
-                "v_max_f32_dpp %1, %4, %1 quad_perm:[0,1,2,3] row_mask:%7 bank_mask:0xf"
+                "v_max_f32_dpp %1, %4, %1 quad_perm:[0,1,2,3] row_mask:%7 bank_mask:0xf\n\t"
+                "s_nop 1"
                 : "+v"(hA), "+v"(hB)
                 : "v"(all), "v"(sA), "v"(sB), "n"(RM_A), "n"(RM_B), "n"(RM_S));
         } else {
             asm("s_nop 1\n\t"
                 "v_max_f32_dpp %0, %2, %0 quad_perm:[0,1,2,3] row_mask:%3 bank_mask:0xf\n\t"
-                "v_max_f32_dpp %1, %2, %1 quad_perm:[0,1,2,3] row_mask:%4 bank_mask:0xf"
+                "v_max_f32_dpp %1, %2, %1 quad_perm:[0,1,2,3] row_mask:%4 bank_mask:0xf\n\t"
+                "s_nop 1"
                 : "+v"(hA), "+v"(hB)
                 : "v"(all), "n"(RM_A), "n"(RM_B));
         }
